@@ -1,0 +1,64 @@
+"""Plain numpy statement of what the SpMM planner must produce (test infrastructure only).
+
+The paper has no planner: it names load balancing and irregular access as the known SpMM
+problems (related-work section) and leaves GPU execution to future work (Section 6).  The
+plan is this build's own structure, so its "oracle" is simply its definition written out
+with sorts, searches and Python loops, no parallel tricks:
+
+  * row length  len_i = rowptr[i+1] - rowptr[i]
+  * class       0 "short" (len <= LW), 1 "wave" (LW < len <= CH), 2 "block" (len > CH)
+  * windows     row i has merge-path key  key_i = rowptr[i] + ALPHA*i  (strictly increasing);
+                window w owns the rows with key in [w*BN, (w+1)*BN); win_row_start[w] is the
+                first such row; there are NW = (nnz + ALPHA*m)//BN + 1 windows
+  * wave_rows   the class-1 row ids, ascending
+  * items       for every class-2 row, ascending: its nnz range cut into pieces of at most BCH;
+                a row cut into more than one piece gets consecutive partial-sum slots
+  * split       (row, first_slot, pieces) for every row with more than one piece, ascending
+
+parity unpinned against the paper (nothing there to pin to); pinned instead by the structural
+invariants in tests/test_plan_oracle.py (every row is covered exactly once, pieces tile the
+row's nnz range, windows partition the rows, bounds on rows and nnz per window).
+"""
+from __future__ import annotations
+
+from typing import Dict
+
+import numpy as np
+
+
+def plan_oracle(rowptr: np.ndarray, BN: int, ALPHA: int, LW: int, CH: int, BCH: int) -> Dict[str, np.ndarray]:
+    rp = np.asarray(rowptr, dtype=np.int64)
+    m = rp.shape[0] - 1
+    nnz = int(rp[-1]) if m >= 0 else 0
+    lens = np.diff(rp)
+    cls = np.where(lens <= LW, 0, np.where(lens <= CH, 1, 2)).astype(np.int32)
+
+    NW = (nnz + ALPHA * m) // BN + 1
+    key = rp[:m] + ALPHA * np.arange(m, dtype=np.int64)
+    win_row_start = np.searchsorted(key, np.arange(NW + 1, dtype=np.int64) * BN, side="left").astype(np.int32)
+    win_row_start[NW] = m
+
+    wave_rows = np.nonzero(cls == 1)[0].astype(np.int32)
+
+    items, split = [], []
+    slot = 0
+    for i in np.nonzero(cls == 2)[0]:
+        p0, p1 = int(rp[i]), int(rp[i + 1])
+        pieces = -(-(p1 - p0) // BCH)
+        if pieces > 1:
+            split.append((int(i), slot, pieces, 0))
+        for c in range(pieces):
+            a = p0 + c * BCH
+            b = min(p1, a + BCH)
+            items.append((int(i), a, b, slot + c if pieces > 1 else -1))
+        if pieces > 1:
+            slot += pieces
+    return {
+        "row_class": cls,
+        "win_row_start": win_row_start,
+        "wave_rows": wave_rows,
+        "items": np.array(items, dtype=np.int32).reshape(-1, 4),
+        "split": np.array(split, dtype=np.int32).reshape(-1, 4),
+        "n_slots": np.int64(slot),
+        "n_short": np.int64(int((cls == 0).sum())),
+    }

@@ -1,0 +1,81 @@
+"""ctypes front end of the plain-C fp64 SpMM oracle (oracle/spmm_oracle.c).
+
+TEST INFRASTRUCTURE ONLY.  Importers allowed: tests/, the smoke check and the cpu_baseline
+leg of the benchmark.  It shares no code with the HIP library.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "spmm_oracle.c")
+_LIB = os.path.join(_HERE, "libspmm_oracle.so")
+_lib = None
+
+
+def oracle_lib_path() -> str:
+    return _LIB
+
+
+def build_oracle(force: bool = False) -> str:
+    """Compile the C oracle with gcc (-O2, strict IEEE: no -ffast-math, no FMA contraction)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + f".tmp{os.getpid()}"
+        subprocess.check_call(["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fPIC", "-shared",
+                               "-o", tmp, _SRC, "-lm"])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        build_oracle()
+        lib = ctypes.CDLL(_LIB)
+        lib.spmm_csr_oracle.restype = ctypes.c_int
+        lib.spmm_csr_oracle.argtypes = [ctypes.c_int64, ctypes.c_int64] + [ctypes.c_void_p] * 4 + \
+            [ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        _lib = lib
+    return _lib
+
+
+def spmm_csr_oracle(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray,
+                    B: np.ndarray, ldb: Optional[int] = None, rows: Optional[np.ndarray] = None,
+                    want_T: bool = True) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+    """C_ref (fp64) and, if asked, T = |A|.|B| (fp64) for all rows or for the listed ``rows``.
+
+    ``B`` is a float32 array holding k rows of stride ``ldb`` (default: its second dimension).
+    """
+    lib = _load()
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    if ldb is None:
+        ldb = B.shape[1] if B.ndim == 2 else n
+    assert rowptr.shape[0] == m + 1
+    nnz = int(rowptr[-1])
+    assert colidx.shape[0] >= nnz and vals.shape[0] >= nnz and ldb >= n
+    if nnz:
+        kmax = int(colidx[:nnz].max())
+        assert int(colidx[:nnz].min()) >= 0 and (kmax + 1) * ldb <= B.size + (ldb - n)
+    if rows is not None:
+        rows = np.ascontiguousarray(rows, dtype=np.int64)
+        count = rows.shape[0]
+        rows_p = rows.ctypes.data
+    else:
+        count = m
+        rows_p = None
+    C = np.empty((count, n), dtype=np.float64)
+    T = np.empty((count, n), dtype=np.float64) if want_T else None
+    rc = lib.spmm_csr_oracle(m, n, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data,
+                             B.ctypes.data, ldb, rows_p, count, C.ctypes.data,
+                             T.ctypes.data if want_T else None)
+    if rc != 0:
+        raise ValueError("spmm_csr_oracle: malformed CSR or row list")
+    return C, T

@@ -1,0 +1,64 @@
+"""Structural invariants that pin the planner's definition (oracle/plan.py)."""
+import numpy as np
+import pytest
+
+from oracle import plan_oracle
+from workloads import csr_from_row_lengths, make_scaled_config
+
+
+def check_plan(rowptr, P, BN, ALPHA, LW, CH, BCH):
+    rp = np.asarray(rowptr, dtype=np.int64)
+    m = rp.shape[0] - 1
+    lens = np.diff(rp)
+    w = P["win_row_start"].astype(np.int64)
+    # windows partition the rows, in order
+    assert w[0] == 0 and w[-1] == m and np.all(np.diff(w) >= 0)
+    assert np.all(np.diff(w) <= -(-BN // ALPHA))  # rows per window bounded
+    for i in range(len(w) - 1):
+        if w[i + 1] > w[i]:
+            span = rp[w[i + 1] - 1] - rp[w[i]]  # distance between first and last row start
+            assert span < BN
+    covered = np.zeros(m, dtype=np.int64)
+    short = lens <= LW
+    covered[short] += 1  # every short row is inside exactly one window (partition above)
+    np.add.at(covered, P["wave_rows"], 1)
+    assert np.all((lens[P["wave_rows"]] > LW) & (lens[P["wave_rows"]] <= CH))
+    assert np.all(np.diff(P["wave_rows"]) > 0)
+    items = P["items"].astype(np.int64)
+    seen_slots = []
+    for row in np.unique(items[:, 0]) if len(items) else []:
+        it = items[items[:, 0] == row]
+        assert lens[row] > CH
+        assert it[0, 1] == rp[row] and it[-1, 2] == rp[row + 1]
+        assert np.all(it[1:, 1] == it[:-1, 2])  # pieces tile the row
+        assert np.all(it[:, 2] - it[:, 1] <= BCH) and np.all(it[:, 2] > it[:, 1])
+        if len(it) == 1:
+            assert it[0, 3] == -1
+        else:
+            assert np.all(np.diff(it[:, 3]) == 1)
+            seen_slots.extend(it[:, 3].tolist())
+            s = P["split"][P["split"][:, 0] == row]
+            assert len(s) == 1 and s[0, 1] == it[0, 3] and s[0, 2] == len(it)
+        covered[row] += 1
+    assert np.all(covered == 1)
+    assert sorted(seen_slots) == list(range(int(P["n_slots"])))
+    assert len(P["split"]) == len({r for r in items[:, 0] if (items[:, 0] == r).sum() > 1}) if len(items) else len(P["split"]) == 0
+
+
+@pytest.mark.parametrize("params", [(128, 4, 32, 128, 512), (64, 2, 16, 64, 64), (256, 8, 64, 1024, 4096)])
+@pytest.mark.parametrize("cfg,scale", [(1, 0.2), (3, 0.03), (4, 0.002)])
+def test_plan_invariants_on_workloads(cfg, scale, params):
+    p = make_scaled_config(cfg, scale, seed=0)
+    BN, ALPHA, LW, CH, BCH = params
+    check_plan(p.rowptr, plan_oracle(p.rowptr, *params), *params)
+
+
+def test_plan_edge_cases():
+    params = (64, 2, 16, 64, 128)
+    for lens in ([0] * 500, [1000], [0, 0, 1000, 0], [17] * 100, [64, 65, 128, 129, 16, 17, 0], []):
+        p = csr_from_row_lengths(lens, 2000, 4, seed=1, duplicates=True)
+        check_plan(p.rowptr, plan_oracle(p.rowptr, *params), *params)
+    P = plan_oracle(csr_from_row_lengths([64, 65, 128, 129, 16, 17, 0], 2000, 4, duplicates=True).rowptr, *params)
+    assert P["row_class"].tolist() == [1, 2, 2, 2, 0, 1, 0]
+    assert P["items"][:, 3].tolist() == [-1, -1, 0, 1]
+    assert P["split"].tolist() == [[3, 0, 2, 0]]
