@@ -1,0 +1,142 @@
+/*
+ * scorch_spmm.h -- C ABI of the MI355X (gfx950) CSR SpMM library.
+ *
+ * Operation (paper, Section 4.2, SpMM example, and the caption of the SpMM tiling figure):
+ *
+ *        C_ik = sum_j A_ij * B_jk
+ *
+ * A is m x k, sparse, stored in CSR: a dense row level and a compressed column level reached
+ * through row pointers (paper, Appendix C "Tensor Formats").  B (k x n) and C (m x n) are dense:
+ * the product of a sparse and a dense matrix is a dense array (paper, Appendix C, format
+ * inference).  The loop order is rows -> stored entries -> dense columns, and only the dense
+ * column loop is tiled (paper, Sections 4.1 and 4.2); here the column loop is spread over the
+ * lanes of a wavefront.
+ *
+ * Conventions shared by every call
+ *   - All array arguments are DEVICE pointers (HIP global memory of the current device) owned by
+ *     the caller; the library never allocates or frees device memory and keeps no reference to
+ *     an argument after the enqueued work has finished, except the plan workspace (below).
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  Work is enqueued
+ *     on it and the call returns without waiting, unless stated otherwise.
+ *   - rowptr: int32[m+1], rowptr[0] = 0, non-decreasing, rowptr[m] = nnz < 2^31.
+ *     colidx: int32[nnz], each in [0, k) (not checked on the device: an index outside [0, k) reads
+ *     outside B).  Entries of a row may be in any order and may repeat;
+ *     every stored entry contributes one term.  vals: float[nnz].
+ *   - B: float, row-major, row stride ldb >= n (elements).  C: float, row-major, row stride
+ *     ldc >= n.  C is overwritten (no alpha/beta); a row without stored entries becomes +0.0;
+ *     columns n..ldc-1 of C and n..ldb-1 of B are never touched.  B and C must not overlap.
+ *   - Arithmetic: fp32 products and fp32 accumulation (fused multiply-add), summation order
+ *     fixed by the plan, so repeated calls give bit-identical results.
+ *   - Return value: SCORCH_OK or a negative status; nothing throws across this boundary.
+ *     On error nothing has been enqueued unless the status is SCORCH_ERR_HIP.
+ *     scorch_last_error() gives a thread-local description of the last failure.
+ *   - m == 0 or n == 0 is valid and does no work.
+ */
+#ifndef SCORCH_SPMM_H
+#define SCORCH_SPMM_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef int32_t scorch_status_t;
+enum {
+    SCORCH_OK = 0,
+    SCORCH_ERR_INVALID_ARG = -1,         /* null pointer, negative size, ldb/ldc < n, ... */
+    SCORCH_ERR_UNSUPPORTED = -2,         /* nnz >= 2^31, or a plan used with other dimensions */
+    SCORCH_ERR_WORKSPACE_TOO_SMALL = -3, /* plan workspace smaller than the stated bound */
+    SCORCH_ERR_HIP = -4                  /* a HIP runtime call failed */
+};
+
+typedef struct scorch_spmm_plan_s scorch_spmm_plan_t; /* small host-side handle */
+
+/*
+ * Plan-free SpMM: C = A.B with one wavefront per row of A in natural row order.  Always
+ * available and correct for any valid input; no load balancing, so rows with very many
+ * entries run on a single wavefront.  (Definition: see the top of this file.)
+ */
+scorch_status_t scorch_spmm_csr(int32_t m, int32_t k, int32_t n,
+                                const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                                const float *B, int32_t ldb,
+                                float *C, int32_t ldc,
+                                void *stream);
+
+/*
+ * Upper bound, in bytes, of the device workspace a plan for (m, nnz, n) needs.  The bound
+ * depends on the tuning read from the environment (see scorch_spmm_plan); call both with the
+ * same environment.  Host-only; touches no device.
+ */
+scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int64_t nnz, int32_t n, size_t *bytes_out);
+
+/*
+ * One-time analysis of a sparsity pattern (the paper names load balance and irregular access
+ * as the SpMM problems, related-work section; its own remedy is CPU-side loop tiling).  Rows
+ * are classed by their stored length:
+ *     short  (len <= LW)        packed into windows of consecutive rows along the merge path
+ *                               key_i = rowptr[i] + ALPHA*i, BN key units per window
+ *     wave   (LW < len <= CH)   one wavefront per row
+ *     block  (len > CH)         cut into pieces of at most BCH entries, one workgroup per piece;
+ *                               rows with several pieces are summed from partial rows in a
+ *                               fixed order (no floating-point atomics)
+ * `workspace` (device, 256-byte aligned, at least the bound above) receives the row lists and
+ * holds the partial rows at execution; it must stay allocated and unmodified while the plan
+ * lives.  `colidx` is not read and may be NULL.  The call enqueues on `stream` and WAITS for it
+ * (it reads nnz and the list sizes back).  The plan is valid for exactly this rowptr content
+ * and this n, on the device that was current.
+ * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=.."
+ * overrides the built-in parameter choice (for experiments).
+ */
+scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
+                                 const int32_t *rowptr, const int32_t *colidx,
+                                 void *workspace, size_t workspace_bytes,
+                                 void *stream,
+                                 scorch_spmm_plan_t **plan_out);
+
+/*
+ * Planned SpMM: same result contract as scorch_spmm_csr, executed through the plan's row lists
+ * (one fused launch, plus one small fix-up launch when rows were split across workgroups).
+ * Never waits, never allocates.  The partial rows live in the plan workspace, so two
+ * executions of one plan must not overlap in time (same stream, or synchronise).
+ */
+scorch_status_t scorch_spmm_csr_planned(const scorch_spmm_plan_t *plan,
+                                        const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                                        const float *B, int32_t ldb,
+                                        float *C, int32_t ldc,
+                                        void *stream);
+
+/* Frees the host handle only (the workspace belongs to the caller).  NULL is accepted. */
+scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan);
+
+/*
+ * What a plan contains.  Offsets are byte offsets into the caller's workspace:
+ *   win_row_start  int32[n_windows + 1]
+ *   wave_rows      int32[n_wave_rows]          ascending row ids
+ *   items          int32[n_items][4]           (row, p_begin, p_end, partial slot or -1)
+ *   split          int32[n_split_rows][4]      (row, first slot, pieces, 0)
+ *   partials       float[n_partial_slots][partial_stride]
+ */
+typedef struct scorch_spmm_plan_info {
+    int32_t m, k, n;
+    int64_t nnz;
+    int32_t BN, ALPHA, LW, CH, BCH;
+    int32_t n_windows, n_short_rows, n_wave_rows, n_items, n_split_rows, n_partial_slots;
+    int32_t partial_stride;
+    uint64_t off_win_row_start, off_wave_rows, off_items, off_split, off_partials;
+    uint64_t workspace_bytes_used;
+} scorch_spmm_plan_info_t;
+
+scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spmm_plan_info_t *out);
+
+/* Static text for a status code. */
+const char *scorch_status_string(scorch_status_t status);
+
+/* Thread-local description of the most recent failure in this thread ("" if none). */
+const char *scorch_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SCORCH_SPMM_H */

@@ -1,0 +1,176 @@
+"""Thin ctypes binding of the C ABI in include/scorch_spmm.h.
+
+Argument marshalling only: every step of the SpMM path runs inside libscorch_spmm.so.  torch is
+used for device memory and streams.  There is no fallback: if the library is missing or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_PKG_DIR = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG_DIR, "libscorch_spmm.so")
+
+SCORCH_OK = 0
+SCORCH_ERR_INVALID_ARG = -1
+SCORCH_ERR_UNSUPPORTED = -2
+SCORCH_ERR_WORKSPACE_TOO_SMALL = -3
+SCORCH_ERR_HIP = -4
+
+EXPORTS = (
+    "scorch_spmm_csr", "scorch_spmm_plan_workspace_bytes", "scorch_spmm_plan", "scorch_spmm_csr_planned",
+    "scorch_spmm_plan_destroy", "scorch_spmm_plan_info", "scorch_status_string", "scorch_last_error",
+)
+
+
+class ScorchError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"scorch status {status}: {message}")
+        self.status = status
+
+
+class PlanInfo(ctypes.Structure):
+    _fields_ = [
+        ("m", ctypes.c_int32), ("k", ctypes.c_int32), ("n", ctypes.c_int32), ("nnz", ctypes.c_int64),
+        ("BN", ctypes.c_int32), ("ALPHA", ctypes.c_int32), ("LW", ctypes.c_int32), ("CH", ctypes.c_int32),
+        ("BCH", ctypes.c_int32),
+        ("n_windows", ctypes.c_int32), ("n_short_rows", ctypes.c_int32), ("n_wave_rows", ctypes.c_int32),
+        ("n_items", ctypes.c_int32), ("n_split_rows", ctypes.c_int32), ("n_partial_slots", ctypes.c_int32),
+        ("partial_stride", ctypes.c_int32),
+        ("off_win_row_start", ctypes.c_uint64), ("off_wave_rows", ctypes.c_uint64), ("off_items", ctypes.c_uint64),
+        ("off_split", ctypes.c_uint64), ("off_partials", ctypes.c_uint64), ("workspace_bytes_used", ctypes.c_uint64),
+    ]
+
+
+_lib = None
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen the in-tree library; raises if it has not been built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2405_16883_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
+    lib.scorch_spmm_csr.restype = i32
+    lib.scorch_spmm_csr.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp]
+    lib.scorch_spmm_plan_workspace_bytes.restype = i32
+    lib.scorch_spmm_plan_workspace_bytes.argtypes = [i32, i64, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.scorch_spmm_plan.restype = i32
+    lib.scorch_spmm_plan.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
+    lib.scorch_spmm_csr_planned.restype = i32
+    lib.scorch_spmm_csr_planned.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp]
+    lib.scorch_spmm_plan_destroy.restype = i32
+    lib.scorch_spmm_plan_destroy.argtypes = [vp]
+    lib.scorch_spmm_plan_info.restype = i32
+    lib.scorch_spmm_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+    lib.scorch_status_string.restype = ctypes.c_char_p
+    lib.scorch_status_string.argtypes = [i32]
+    lib.scorch_last_error.restype = ctypes.c_char_p
+    lib.scorch_last_error.argtypes = []
+    _lib = lib
+    return lib
+
+
+def _check(status: int) -> None:
+    if status != SCORCH_OK:
+        lib = load_library()
+        raise ScorchError(status, f"{lib.scorch_status_string(status).decode()}: {lib.scorch_last_error().decode()}")
+
+
+def _dev_ptr(t: Optional[torch.Tensor], dtype: torch.dtype, name: str) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError(f"{name} must live on the GPU")
+    if t.dtype != dtype:
+        raise ValueError(f"{name} must be {dtype}, got {t.dtype}")
+    return t.data_ptr() if t.numel() else None
+
+
+def _ld(t: torch.Tensor, name: str) -> int:
+    if t.dim() != 2 or (t.numel() and t.stride(1) != 1):
+        raise ValueError(f"{name} must be 2-D with unit column stride")
+    return int(t.stride(0)) if t.shape[0] > 1 else max(int(t.stride(0)), int(t.shape[1]))
+
+
+def _stream_handle(stream: Optional[torch.cuda.Stream]) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def scorch_spmm_csr(m: int, k: int, n: int, rowptr: torch.Tensor, colidx: torch.Tensor, vals: torch.Tensor,
+                    B: torch.Tensor, C: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """C[:m, :n] = A @ B[:k, :n] through the plan-free entry point.  B and C may be row-strided views."""
+    lib = load_library()
+    _check(lib.scorch_spmm_csr(m, k, n, _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+                               _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(B, torch.float32, "B"), _ld(B, "B"),
+                               _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))
+
+
+def scorch_spmm_plan_workspace_bytes(m: int, nnz: int, n: int) -> int:
+    lib = load_library()
+    out = ctypes.c_size_t(0)
+    _check(lib.scorch_spmm_plan_workspace_bytes(m, nnz, n, ctypes.byref(out)))
+    return int(out.value)
+
+
+class SpmmPlan:
+    """Owns the C plan handle and the torch tensor that backs its device workspace."""
+
+    def __init__(self, handle: int, workspace: torch.Tensor):
+        self._handle = handle
+        self.workspace = workspace
+
+    @property
+    def handle(self) -> int:
+        if not self._handle:
+            raise ValueError("plan already destroyed")
+        return self._handle
+
+    def info(self) -> PlanInfo:
+        out = PlanInfo()
+        _check(load_library().scorch_spmm_plan_info(self.handle, ctypes.byref(out)))
+        return out
+
+    def destroy(self) -> None:
+        if self._handle:
+            load_library().scorch_spmm_plan_destroy(self._handle)
+            self._handle = 0
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def scorch_spmm_plan(m: int, k: int, n: int, rowptr: torch.Tensor, nnz: int,
+                     workspace: Optional[torch.Tensor] = None,
+                     stream: Optional[torch.cuda.Stream] = None) -> SpmmPlan:
+    """Analyse the pattern behind ``rowptr``.  ``workspace`` (uint8, GPU) is allocated with torch if not given."""
+    lib = load_library()
+    if workspace is None:
+        workspace = torch.empty(scorch_spmm_plan_workspace_bytes(m, nnz, n), dtype=torch.uint8, device=rowptr.device)
+    handle = ctypes.c_void_p(0)
+    _check(lib.scorch_spmm_plan(m, k, n, _dev_ptr(rowptr, torch.int32, "rowptr"), None,
+                                _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
+                                _stream_handle(stream), ctypes.byref(handle)))
+    return SpmmPlan(handle.value, workspace)
+
+
+def scorch_spmm_csr_planned(plan: SpmmPlan, rowptr: torch.Tensor, colidx: torch.Tensor, vals: torch.Tensor,
+                            B: torch.Tensor, C: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    lib = load_library()
+    _check(lib.scorch_spmm_csr_planned(plan.handle, _dev_ptr(rowptr, torch.int32, "rowptr"),
+                                       _dev_ptr(colidx, torch.int32, "colidx"), _dev_ptr(vals, torch.float32, "vals"),
+                                       _dev_ptr(B, torch.float32, "B"), _ld(B, "B"),
+                                       _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))

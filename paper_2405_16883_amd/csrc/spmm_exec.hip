@@ -1,0 +1,482 @@
+// Execution kernels for CSR SpMM on gfx950:  C_ik = sum_j A_ij * B_jk  (paper, Section 4.2).
+//
+// Loop structure kept from the paper (Sections 4.1, 4.2): rows outermost, the stored entries of a
+// row next, the dense column index innermost, and only that dense column loop is tiled.  On the
+// GPU the column loop is laid across lanes: a group of G lanes covers G*V*T consecutive columns
+// (V floats per load, T loads per lane), so every read of a B row and every write of a C row is a
+// contiguous, coalesced burst.  A wavefront holds S = 64/G such groups.
+//
+// Three paths share one launch; the workgroup index selects the path:
+//   items   one workgroup per piece of a long row; 4 wavefronts split the piece, partial sums are
+//           combined through LDS and written to C or to a partial row
+//   wave    one wavefront per medium row; the S groups take interleaved entries and are combined
+//           with cross-lane shuffles
+//   window  one wavefront per window of consecutive short rows; the window's colidx/vals are
+//           staged in LDS with coalesced loads, then each group walks one row at a time
+// No MFMA: the work is a gather, not a dense contraction.  No atomics: summation order is fixed.
+#include "spmm_internal.h"
+
+namespace scorch {
+
+template <int V> struct Vec;
+template <> struct Vec<1> { using type = float; };
+template <> struct Vec<2> { typedef float type __attribute__((ext_vector_type(2))); };
+template <> struct Vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+
+template <int V> __device__ __forceinline__ typename Vec<V>::type vzero() {
+    typename Vec<V>::type z;
+    if constexpr (V == 1) z = 0.f;
+    else for (int i = 0; i < V; ++i) z[i] = 0.f;
+    return z;
+}
+template <int V> __device__ __forceinline__ void vfma(typename Vec<V>::type &acc, float a, const typename Vec<V>::type &x) {
+    if constexpr (V == 1) acc = __builtin_fmaf(a, x, acc);
+    else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] = __builtin_fmaf(a, x[i], acc[i]);
+    }
+}
+template <int V> __device__ __forceinline__ void vadd(typename Vec<V>::type &acc, const typename Vec<V>::type &x) {
+    if constexpr (V == 1) acc += x;
+    else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) acc[i] += x[i];
+    }
+}
+template <int V> __device__ __forceinline__ typename Vec<V>::type vshfl_xor(const typename Vec<V>::type &x, int off) {
+    typename Vec<V>::type r;
+    if constexpr (V == 1) r = __shfl_xor(x, off, kWave);
+    else {
+#pragma unroll
+        for (int i = 0; i < V; ++i) r[i] = __shfl_xor(x[i], off, kWave);
+    }
+    return r;
+}
+template <int V> __device__ __forceinline__ typename Vec<V>::type vload(const float *p) {
+    return *reinterpret_cast<const typename Vec<V>::type *>(p);
+}
+template <int V, bool NT> __device__ __forceinline__ void vstore(float *p, const typename Vec<V>::type &x) {
+    auto *q = reinterpret_cast<typename Vec<V>::type *>(p);
+    if constexpr (NT) __builtin_nontemporal_store(x, q);
+    else *q = x;
+}
+template <bool NT> __device__ __forceinline__ int ld_idx(const int32_t *p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+template <bool NT> __device__ __forceinline__ float ld_val(const float *p) {
+    if constexpr (NT) return __builtin_nontemporal_load(p);
+    else return *p;
+}
+
+// Orders LDS writes before later LDS reads of other lanes of the same wavefront.  LDS operations
+// of one wavefront execute in program order, so only the compiler has to be held back.
+__device__ __forceinline__ void wave_lds_sync() {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// One lane group accumulates the staged entries e0, e0+es, ... (< e_end) of a row:
+//   acc[t] += val[e] * B[col[e], c0 + t*G*V .. +V)
+// U gathers are issued before the first multiply so that U B-row reads are in flight per group.
+template <int V, int GV, int T, int U>
+__device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
+                                           int e0, int e_end, int es, const float *Bc, int64_t ldb,
+                                           const bool (&colok)[T]) {
+    using vec = typename Vec<V>::type;
+    for (int e = e0; e < e_end; e += es * U) {
+        vec x[U][T];
+        float v[U];
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            const int ee = e + u * es;
+            const bool ok = ee < e_end;
+            const int c = lcol[ok ? ee : e0];
+            v[u] = ok ? lval[ee] : 0.f;
+            const float *bp = Bc + (int64_t)c * ldb;
+#pragma unroll
+            for (int t = 0; t < T; ++t) x[u][t] = (ok && colok[t]) ? vload<V>(bp + t * GV) : vzero<V>();
+        }
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+#pragma unroll
+            for (int t = 0; t < T; ++t) vfma<V>(acc[t], v[u], x[u][t]);
+    }
+}
+
+template <int V, int G, int T>
+__device__ __forceinline__ void reduce_groups(typename Vec<V>::type (&acc)[T]) {
+#pragma unroll
+    for (int off = G; off < kWave; off <<= 1)
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            auto o = vshfl_xor<V>(acc[t], off);
+            vadd<V>(acc[t], o);
+        }
+}
+
+// A wavefront walks the entries [p0 + first, p1) of one row in chunks of 64 that are `stride`
+// apart (stride = 64 for a whole wavefront-row, 256 when 4 wavefronts share a piece).  Each chunk
+// is read with one coalesced load per array, parked in LDS, and broadcast from there to the lane
+// groups; the next chunk is fetched into registers while the current one is consumed.
+template <int V, int G, int T, int U, bool NTA>
+__device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], int *lcol, float *lval, int lane,
+                                               int grp, int pfirst, int p1, int stride, const int32_t *colidx,
+                                               const float *vals, const float *Bc, int64_t ldb,
+                                               const bool (&colok)[T]) {
+    constexpr int S = kWave / G;
+    int pc = pfirst + lane;
+    int cn = 0;
+    float vn = 0.f;
+    if (pc < p1) {
+        cn = ld_idx<NTA>(colidx + pc);
+        vn = ld_val<NTA>(vals + pc);
+    }
+    for (int base = pfirst; base < p1; base += stride) {
+        lcol[lane] = cn;
+        lval[lane] = vn;
+        pc = base + stride + lane;
+        if (pc < p1) {
+            cn = ld_idx<NTA>(colidx + pc);
+            vn = ld_val<NTA>(vals + pc);
+        }
+        wave_lds_sync();
+        const int cnt = min(kWave, p1 - base);
+        gather_fma<V, G * V, T, U>(acc, lcol, lval, grp, cnt, S, Bc, ldb, colok);
+        wave_lds_sync();
+    }
+}
+
+constexpr int smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
+
+template <int V, int G, int T, int U, int NT>
+__global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
+    using vec = typename Vec<V>::type;
+    constexpr int S = kWave / G;
+    constexpr int GV = G * V;
+    constexpr int TW = GV * T;
+    constexpr bool NTC = (NT & 1) != 0;
+    constexpr bool NTA = (NT & 2) != 0;
+
+    __shared__ int s_raw[kWavesPerBlock * smem_ints_per_wave()];
+    __shared__ float s_red[kWavesPerBlock * TW];
+
+    const int tid = threadIdx.x;
+    const int wv = tid >> 6;
+    const int lane = tid & 63;
+    const int grp = lane / G;
+    const int lig = lane % G;
+
+    const uint32_t per_tile = (uint32_t)a.nb_items + (uint32_t)a.nb_wave + (uint32_t)a.nb_win;
+    const uint32_t ct = blockIdx.x / per_tile;
+    const uint32_t b = blockIdx.x - ct * per_tile;
+
+    const int c0 = (int)ct * TW + lig * V;
+    bool colok[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) colok[t] = (c0 + t * GV) < a.n;
+    const float *Bc = a.B + c0;
+
+    int *lcol = s_raw + wv * smem_ints_per_wave();
+    float *lval = reinterpret_cast<float *>(lcol + kStageMax);
+    int *lrp = lcol + 2 * kStageMax;
+
+    vec acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
+
+    if (b < (uint32_t)a.nb_items) {
+        // ---- piece of a long row: 4 wavefronts, LDS tree, then C or a partial row ----
+        const int4 it = a.items[b];
+        row_accumulate<V, G, T, U, NTA>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
+                                        a.vals, Bc, a.ldb, colok);
+        reduce_groups<V, G, T>(acc);
+        if (grp == 0) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if constexpr (V == 1) s_red[wv * TW + t * GV + lig] = acc[t];
+                else
+#pragma unroll
+                    for (int i = 0; i < V; ++i) s_red[wv * TW + t * GV + lig * V + i] = acc[t][i];
+            }
+        }
+        __syncthreads();
+        if (wv == 0 && grp == 0) {
+            float *dst = it.w < 0 ? a.C + (int64_t)it.x * a.ldc + c0
+                                  : a.partials + (int64_t)it.w * a.partial_stride + c0;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if (!colok[t]) continue;
+                vec r;
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const int o = t * GV + lig * V + i;
+                    float s = s_red[o];
+#pragma unroll
+                    for (int w = 1; w < kWavesPerBlock; ++w) s += s_red[w * TW + o];
+                    if constexpr (V == 1) r = s;
+                    else r[i] = s;
+                }
+                vstore<V, NTC>(dst + t * GV, r);
+            }
+        }
+        return;
+    }
+
+    if (b < (uint32_t)(a.nb_items + a.nb_wave)) {
+        // ---- medium row: one wavefront, groups interleave entries, shuffle reduction ----
+        const int idx = (int)(b - a.nb_items) * kWavesPerBlock + wv;
+        if (idx >= a.n_wave_rows) return;
+        const int row = a.wave_rows[idx];
+        const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
+        row_accumulate<V, G, T, U, NTA>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, a.ldb,
+                                        colok);
+        reduce_groups<V, G, T>(acc);
+        if (grp == 0) {
+            float *dst = a.C + (int64_t)row * a.ldc + c0;
+#pragma unroll
+            for (int t = 0; t < T; ++t)
+                if (colok[t]) vstore<V, NTC>(dst + t * GV, acc[t]);
+        }
+        return;
+    }
+
+    // ---- window of consecutive short rows ----
+    const int w = (int)(b - a.nb_items - a.nb_wave) * kWavesPerBlock + wv;
+    if (w >= a.n_windows) return;
+    const int r0 = a.win_row_start[w];
+    const int r1 = a.win_row_start[w + 1];
+    const int nr = min(r1 - r0, kWindowRowsMax);
+    if (nr <= 0) return;
+    const int rpv = a.rowptr[r0 + min(lane, nr)];
+    const int rlast = a.rowptr[r0 + nr];
+    int rnext = __shfl_down(rpv, 1, kWave);
+    if (lane == kWave - 1) rnext = rlast;
+    const bool is_short = lane < nr && (rnext - rpv) <= a.LW;
+    const unsigned long long bal = __ballot(is_short);
+    if (bal == 0ull) return;
+    const int first = __builtin_ctzll(bal);
+    const int last = 63 - __builtin_clzll(bal);
+    const int sbeg = __shfl(rpv, first, kWave);
+    const int send = __shfl(rnext, last, kWave);
+    const int cnt = min(send - sbeg, kStageMax);
+    for (int e = lane; e < cnt; e += kWave) {
+        lcol[e] = ld_idx<NTA>(a.colidx + sbeg + e);
+        lval[e] = ld_val<NTA>(a.vals + sbeg + e);
+    }
+    lrp[lane] = rpv;
+    if (lane == 0) lrp[nr] = rlast;
+    wave_lds_sync();
+    for (int ri = grp; ri < nr; ri += S) {
+        const int q0 = lrp[ri], q1 = lrp[ri + 1];
+        if (q1 - q0 > a.LW) continue;  // medium/long row: handled by another path
+#pragma unroll
+        for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
+        gather_fma<V, GV, T, U>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, a.ldb, colok);
+        float *dst = a.C + (int64_t)(r0 + ri) * a.ldc + c0;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+            if (colok[t]) vstore<V, NTC>(dst + t * GV, acc[t]);
+    }
+}
+
+// Plan-free path: one wavefront per row in natural order (any row length).
+template <int V, int G, int T, int U, int NT>
+__global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) {
+    using vec = typename Vec<V>::type;
+    constexpr int GV = G * V;
+    constexpr int TW = GV * T;
+    constexpr bool NTC = (NT & 1) != 0;
+    constexpr bool NTA = (NT & 2) != 0;
+    __shared__ int s_col[kWavesPerBlock * kWave];
+    __shared__ float s_val[kWavesPerBlock * kWave];
+    const int tid = threadIdx.x;
+    const int wv = tid >> 6;
+    const int lane = tid & 63;
+    const int grp = lane / G;
+    const int lig = lane % G;
+    const uint32_t per_tile = (uint32_t)a.nb_wave;
+    const uint32_t ct = blockIdx.x / per_tile;
+    const uint32_t b = blockIdx.x - ct * per_tile;
+    const int64_t row = (int64_t)b * kWavesPerBlock + wv;
+    if (row >= a.m) return;
+    const int c0 = (int)ct * TW + lig * V;
+    bool colok[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) colok[t] = (c0 + t * GV) < a.n;
+    vec acc[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
+    const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
+    row_accumulate<V, G, T, U, NTA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, p0, p1, kWave,
+                                    a.colidx, a.vals, a.B + c0, a.ldb, colok);
+    reduce_groups<V, G, T>(acc);
+    if (grp == 0) {
+        float *dst = a.C + row * a.ldc + c0;
+#pragma unroll
+        for (int t = 0; t < T; ++t)
+            if (colok[t]) vstore<V, NTC>(dst + t * GV, acc[t]);
+    }
+}
+
+// Rows cut into several pieces: add the partial rows in piece order.
+__global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const FixupArgs a) {
+    const int s = blockIdx.x;
+    if (s >= a.n_split) return;
+    const int4 d = a.split[s];
+    const float *src = a.partials + (int64_t)d.y * a.partial_stride;
+    float *dst = a.C + (int64_t)d.x * a.ldc;
+    for (int c = threadIdx.x; c < a.n; c += kBlock) {
+        float sum = src[c];
+        for (int i = 1; i < d.z; ++i) sum += src[(int64_t)i * a.partial_stride + c];
+        dst[c] = sum;
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// host side: pick the lane mapping from n and the operand alignment, then launch
+// ------------------------------------------------------------------------------------------
+struct Mapping {
+    int V, G, T, ncoltiles;
+};
+
+static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc) {
+    Mapping mp;
+    const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(C);
+    if (n % 4 == 0 && ldb % 4 == 0 && ldc % 4 == 0 && pb % 16 == 0 && pc % 16 == 0) mp.V = 4;
+    else if (n % 2 == 0 && ldb % 2 == 0 && ldc % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) mp.V = 2;
+    else mp.V = 1;
+    const int lanes = (n + mp.V - 1) / mp.V;
+    if (lanes <= kWave) {
+        int g = 4;
+        while (g < lanes) g <<= 1;
+        mp.G = g;
+        mp.T = 1;
+        mp.ncoltiles = 1;
+    } else {
+        mp.G = kWave;
+        mp.T = lanes > kWave ? 2 : 1;
+        const int tw = mp.G * mp.V * mp.T;
+        mp.ncoltiles = (n + tw - 1) / tw;
+    }
+    return mp;
+}
+
+typedef void (*kernel_fn)(const ExecArgs);
+
+#define SCORCH_PICK_NT(KERNEL, V, G, T, U)                                  \
+    switch (NT & 3) {                                                       \
+        case 0: return KERNEL<V, G, T, U, 0>;                               \
+        case 1: return KERNEL<V, G, T, U, 1>;                               \
+        case 2: return KERNEL<V, G, T, U, 2>;                               \
+        default: return KERNEL<V, G, T, U, 3>;                              \
+    }
+#define SCORCH_PICK_U(KERNEL, V, G, T)                                      \
+    if (U >= 8) { SCORCH_PICK_NT(KERNEL, V, G, T, 8) } else { SCORCH_PICK_NT(KERNEL, V, G, T, 4) }
+#define SCORCH_PICK_G(KERNEL, V)                                            \
+    if (T == 2) { SCORCH_PICK_U(KERNEL, V, 64, 2) }                         \
+    switch (G) {                                                            \
+        case 4: SCORCH_PICK_U(KERNEL, V, 4, 1)                              \
+        case 8: SCORCH_PICK_U(KERNEL, V, 8, 1)                              \
+        case 16: SCORCH_PICK_U(KERNEL, V, 16, 1)                            \
+        case 32: SCORCH_PICK_U(KERNEL, V, 32, 1)                            \
+        default: SCORCH_PICK_U(KERNEL, V, 64, 1)                            \
+    }
+#define SCORCH_PICK(KERNEL)                                                 \
+    switch (V) {                                                            \
+        case 4: SCORCH_PICK_G(KERNEL, 4)                                    \
+        case 2: SCORCH_PICK_G(KERNEL, 2)                                    \
+        default: SCORCH_PICK_G(KERNEL, 1)                                   \
+    }
+
+static kernel_fn pick_fused(int V, int G, int T, int U, int NT) { SCORCH_PICK(spmm_fused_kernel) }
+static kernel_fn pick_natural(int V, int G, int T, int U, int NT) { SCORCH_PICK(spmm_natural_kernel) }
+
+static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
+                               const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
+                               hipStream_t stream) {
+    const Mapping mp = pick_mapping(plan->n, B, ldb, C, ldc);
+    ExecArgs a{};
+    a.rowptr = rowptr;
+    a.colidx = colidx;
+    a.vals = vals;
+    a.B = B;
+    a.C = C;
+    a.ldb = ldb;
+    a.ldc = ldc;
+    a.m = plan->m;
+    a.n = plan->n;
+    char *ws = plan->workspace;
+    a.win_row_start = reinterpret_cast<const int32_t *>(ws + plan->layout.off_win);
+    a.wave_rows = reinterpret_cast<const int32_t *>(ws + plan->layout.off_wave);
+    a.items = reinterpret_cast<const int4 *>(ws + plan->layout.off_items);
+    a.partials = reinterpret_cast<float *>(ws + plan->layout.off_partials);
+    a.n_windows = (int32_t)plan->layout.n_windows;
+    a.n_wave_rows = plan->n_wave;
+    a.n_items = plan->n_items;
+    a.nb_items = plan->n_items;
+    a.nb_wave = (int32_t)ceil_div64(plan->n_wave, kWavesPerBlock);
+    a.nb_win = plan->n_short > 0 ? (int32_t)ceil_div64(plan->layout.n_windows, kWavesPerBlock) : 0;
+    a.partial_stride = plan->layout.partial_stride;
+    a.LW = plan->params.LW;
+    a.ncoltiles = mp.ncoltiles;
+    const int64_t per_tile = (int64_t)a.nb_items + a.nb_wave + a.nb_win;
+    const int64_t grid = per_tile * mp.ncoltiles;
+    if (grid > 0x7fffffffLL) {
+        set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);
+        return SCORCH_ERR_UNSUPPORTED;
+    }
+    if (grid > 0) {
+        kernel_fn fn = pick_fused(mp.V, mp.G, mp.T, plan->params.U, plan->params.NT);
+        hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "launch spmm_fused_kernel");
+    }
+    if (plan->n_split > 0) {
+        FixupArgs f{};
+        f.split = reinterpret_cast<const int4 *>(ws + plan->layout.off_split);
+        f.partials = a.partials;
+        f.C = C;
+        f.ldc = ldc;
+        f.n = plan->n;
+        f.n_split = plan->n_split;
+        f.partial_stride = plan->layout.partial_stride;
+        hipLaunchKernelGGL(spmm_fixup_kernel, dim3((uint32_t)plan->n_split), dim3(kBlock), 0, stream, f);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "launch spmm_fixup_kernel");
+    }
+    return SCORCH_OK;
+}
+
+scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
+                               const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
+                               int32_t U, int32_t NT, hipStream_t stream) {
+    const Mapping mp = pick_mapping(n, B, ldb, C, ldc);
+    ExecArgs a{};
+    a.rowptr = rowptr;
+    a.colidx = colidx;
+    a.vals = vals;
+    a.B = B;
+    a.C = C;
+    a.ldb = ldb;
+    a.ldc = ldc;
+    a.m = m;
+    a.n = n;
+    a.nb_wave = (int32_t)ceil_div64(m, kWavesPerBlock);
+    a.ncoltiles = mp.ncoltiles;
+    const int64_t grid = (int64_t)a.nb_wave * mp.ncoltiles;
+    if (grid > 0x7fffffffLL) {
+        set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);
+        return SCORCH_ERR_UNSUPPORTED;
+    }
+    kernel_fn fn = pick_natural(mp.V, mp.G, mp.T, U, NT);
+    hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "launch spmm_natural_kernel");
+    return SCORCH_OK;
+}
+
+}  // namespace scorch

@@ -1,0 +1,102 @@
+// Internal declarations shared by the planner, the execution kernels and the C entry points.
+// gfx950 only: 64-wide wavefronts, 256-thread workgroups (4 wavefronts).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "scorch_spmm.h"
+
+namespace scorch {
+
+constexpr int kWave = 64;
+constexpr int kWavesPerBlock = 4;
+constexpr int kBlock = kWave * kWavesPerBlock;
+// A window stages at most BN + LW entries per wavefront in LDS.
+constexpr int kBNMax = 256;
+constexpr int kLWMax = 64;
+constexpr int kStageMax = kBNMax + kLWMax;
+constexpr int kWindowRowsMax = 64;  // one lane per row when reading rowptr
+
+// Parameters that decide how rows are classed and cut (paper has none of this; see the header).
+struct PlanParams {
+    int32_t BN;     // merge-path key units per window
+    int32_t ALPHA;  // key weight of one row: key_i = rowptr[i] + ALPHA*i
+    int32_t LW;     // short rows: len <= LW
+    int32_t CH;     // wave rows:  LW < len <= CH
+    int32_t BCH;    // block rows: pieces of at most BCH entries
+    int32_t U;      // gathers in flight per lane group (4 or 8)
+    int32_t NT;     // bit 0: streaming stores for C; bit 1: streaming loads for colidx/vals
+};
+
+struct Tuning {
+    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1;
+};
+Tuning read_tuning_from_env();
+PlanParams choose_params(int32_t m, int64_t nnz, int32_t n, const Tuning &t);
+
+struct WorkspaceLayout {
+    uint64_t off_counts, off_totals, off_win, off_wave, off_items, off_split, off_partials, total;
+    int64_t n_windows, nblk;
+    int64_t cap_wave, cap_items, cap_split, cap_slots;
+    int32_t partial_stride;
+};
+WorkspaceLayout layout_workspace(int32_t m, int64_t nnz, int32_t n, const PlanParams &p);
+
+// Everything the execution kernels need, passed by value.
+struct ExecArgs {
+    const int32_t *rowptr;
+    const int32_t *colidx;
+    const float *vals;
+    const float *B;
+    float *C;
+    int64_t ldb, ldc;
+    int32_t m, n;
+    const int32_t *win_row_start;
+    const int32_t *wave_rows;
+    const int4 *items;
+    float *partials;
+    int32_t n_windows, n_wave_rows, n_items;
+    int32_t nb_items, nb_wave, nb_win;  // workgroups per path, per column tile
+    int32_t partial_stride;
+    int32_t LW;
+    int32_t ncoltiles;
+};
+
+struct FixupArgs {
+    const int4 *split;
+    const float *partials;
+    float *C;
+    int64_t ldc;
+    int32_t n, n_split, partial_stride;
+};
+
+}  // namespace scorch
+
+struct scorch_spmm_plan_s {
+    int32_t m, k, n;
+    int64_t nnz;
+    int device;
+    scorch::PlanParams params;
+    scorch::WorkspaceLayout layout;
+    char *workspace;
+    int32_t n_short, n_wave, n_items, n_split, n_slots;
+};
+
+namespace scorch {
+
+void set_error(const char *fmt, ...);
+scorch_status_t hip_fail(hipError_t e, const char *what);
+
+// spmm_plan.hip
+scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, hipStream_t stream);
+
+// spmm_exec.hip
+scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
+                               const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
+                               hipStream_t stream);
+scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
+                               const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
+                               int32_t U, int32_t NT, hipStream_t stream);
+
+}  // namespace scorch

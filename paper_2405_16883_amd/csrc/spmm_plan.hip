@@ -1,0 +1,317 @@
+// Planner: one-time analysis of a CSR sparsity pattern on the device.
+//
+// The paper's remedy for SpMM cost is CPU-side loop ordering and tiling (Sections 4.1, 4.2); it
+// names load balance and irregular access as the open problems of sparse kernels (related-work
+// section).  On a GPU the skew of row lengths decides everything, so rows are classed by length
+// and handed to different execution paths (see spmm_exec.hip):
+//   short  len <= LW       -> windows of consecutive rows, cut along the merge path
+//                             key_i = rowptr[i] + ALPHA*i every BN key units
+//   wave   LW < len <= CH  -> ascending list of row ids, one wavefront each
+//   block  len > CH        -> pieces of at most BCH entries; a row with several pieces gets
+//                             consecutive partial-row slots and an entry in the split list
+// All lists come out in ascending row order (stable compaction), so the plan is a pure function
+// of rowptr and the parameters.
+#include "spmm_internal.h"
+
+#include <algorithm>
+#include <cstdlib>
+#include <cstring>
+
+namespace scorch {
+
+constexpr int kQ = 5;  // counted quantities: wave rows, items, split rows, slots, short rows
+
+struct PlanArgs {
+    const int32_t *rowptr;
+    int32_t m;
+    int32_t LW, CH, BCH;
+    int64_t nblk;
+    int32_t *counts;  // [kQ][nblk], turned into exclusive offsets by the scan
+    int32_t *totals;  // [kQ]
+    int32_t *wave_rows;
+    int4 *items;
+    int4 *split;
+    int64_t cap_wave, cap_items, cap_split;  // list capacities: writes beyond them are dropped
+};
+
+struct RowClass {
+    int wave, items, split, slots, is_short;
+};
+
+__device__ __forceinline__ RowClass classify(int len, int LW, int CH, int BCH) {
+    RowClass r{0, 0, 0, 0, 0};
+    if (len <= LW) r.is_short = 1;
+    else if (len <= CH) r.wave = 1;
+    else {
+        r.items = (len + BCH - 1) / BCH;
+        if (r.items > 1) {
+            r.split = 1;
+            r.slots = r.items;
+        }
+    }
+    return r;
+}
+
+// Exclusive prefix sum over the 256 threads of a workgroup; `total` is the workgroup sum.
+__device__ __forceinline__ int block_exclusive_scan(int v, int &total, int *s_wave /*[4]*/) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const int o = __shfl_up(inc, off, kWave);
+        if (lane >= off) inc += o;
+    }
+    __syncthreads();
+    if (lane == kWave - 1) s_wave[wv] = inc;
+    __syncthreads();
+    int base = 0;
+    total = 0;
+#pragma unroll
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        const int t = s_wave[w];
+        if (w < wv) base += t;
+        total += t;
+    }
+    return base + inc - v;
+}
+
+__global__ __launch_bounds__(kBlock) void plan_count_kernel(const PlanArgs a) {
+    __shared__ int s_wave[kWavesPerBlock];
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    RowClass rc{0, 0, 0, 0, 0};
+    if (i < a.m) rc = classify(a.rowptr[i + 1] - a.rowptr[i], a.LW, a.CH, a.BCH);
+    const int q[kQ] = {rc.wave, rc.items, rc.split, rc.slots, rc.is_short};
+#pragma unroll
+    for (int k = 0; k < kQ; ++k) {
+        int total;
+        (void)block_exclusive_scan(q[k], total, s_wave);
+        if (threadIdx.x == 0) a.counts[(int64_t)k * a.nblk + blockIdx.x] = total;
+    }
+}
+
+// One workgroup turns each of the kQ count arrays into exclusive offsets and stores the totals.
+__global__ __launch_bounds__(1024) void plan_scan_kernel(const PlanArgs a) {
+    __shared__ int s_part[1024];
+    const int tid = threadIdx.x;
+    const int64_t per = (a.nblk + 1023) / 1024;
+    for (int k = 0; k < kQ; ++k) {
+        int32_t *c = a.counts + (int64_t)k * a.nblk;
+        const int64_t lo = std::min<int64_t>((int64_t)tid * per, a.nblk);
+        const int64_t hi = std::min<int64_t>(lo + per, a.nblk);
+        int sum = 0;
+        for (int64_t j = lo; j < hi; ++j) sum += c[j];
+        s_part[tid] = sum;
+        __syncthreads();
+        if (tid == 0) {
+            int run = 0;
+            for (int j = 0; j < 1024; ++j) {
+                const int t = s_part[j];
+                s_part[j] = run;
+                run += t;
+            }
+            a.totals[k] = run;
+        }
+        __syncthreads();
+        int run = s_part[tid];
+        for (int64_t j = lo; j < hi; ++j) {
+            const int t = c[j];
+            c[j] = run;
+            run += t;
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(kBlock) void plan_scatter_kernel(const PlanArgs a) {
+    __shared__ int s_wave[kWavesPerBlock];
+    const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    RowClass rc{0, 0, 0, 0, 0};
+    int p0 = 0, p1 = 0;
+    if (i < a.m) {
+        p0 = a.rowptr[i];
+        p1 = a.rowptr[i + 1];
+        rc = classify(p1 - p0, a.LW, a.CH, a.BCH);
+    }
+    int total;
+    const int pos_wave = a.counts[0 * a.nblk + blockIdx.x] + block_exclusive_scan(rc.wave, total, s_wave);
+    const int pos_item = a.counts[1 * a.nblk + blockIdx.x] + block_exclusive_scan(rc.items, total, s_wave);
+    const int pos_split = a.counts[2 * a.nblk + blockIdx.x] + block_exclusive_scan(rc.split, total, s_wave);
+    const int pos_slot = a.counts[3 * a.nblk + blockIdx.x] + block_exclusive_scan(rc.slots, total, s_wave);
+    // The capacities hold for every valid rowptr; the guards only keep a malformed one in bounds
+    // (the host then reports the overflow from the totals).
+    if (rc.wave && pos_wave < a.cap_wave) a.wave_rows[pos_wave] = (int)i;
+    for (int c = 0; c < rc.items && (int64_t)pos_item + c < a.cap_items; ++c) {
+        const int b = p0 + c * a.BCH;
+        a.items[pos_item + c] = make_int4((int)i, b, min(p1, b + a.BCH), rc.split ? pos_slot + c : -1);
+    }
+    if (rc.split && pos_split < a.cap_split) a.split[pos_split] = make_int4((int)i, pos_slot, rc.items, 0);
+}
+
+// win_row_start[w] = number of rows whose key rowptr[i] + ALPHA*i is below w*BN.
+__global__ __launch_bounds__(kBlock) void plan_window_kernel(const int32_t *rowptr, int32_t m, int32_t BN,
+                                                             int32_t ALPHA, int64_t n_windows,
+                                                             int32_t *win_row_start) {
+    const int64_t w = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (w > n_windows) return;
+    if (w == n_windows) {
+        win_row_start[w] = m;
+        return;
+    }
+    const int64_t target = w * (int64_t)BN;
+    int64_t lo = 0, hi = m;
+    while (lo < hi) {
+        const int64_t mid = (lo + hi) >> 1;
+        const int64_t key = (int64_t)rowptr[mid] + (int64_t)ALPHA * mid;
+        if (key < target) lo = mid + 1;
+        else hi = mid;
+    }
+    win_row_start[w] = (int32_t)lo;
+}
+
+// ------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------
+Tuning read_tuning_from_env() {
+    Tuning t;
+    const char *s = std::getenv("SCORCH_SPMM_TUNE");
+    if (!s) return t;
+    char buf[256];
+    std::strncpy(buf, s, sizeof(buf) - 1);
+    buf[sizeof(buf) - 1] = 0;
+    for (char *tok = std::strtok(buf, ","); tok; tok = std::strtok(nullptr, ",")) {
+        char *eq = std::strchr(tok, '=');
+        if (!eq) continue;
+        *eq = 0;
+        const int v = std::atoi(eq + 1);
+        if (!std::strcmp(tok, "bn")) t.bn = v;
+        else if (!std::strcmp(tok, "alpha")) t.alpha = v;
+        else if (!std::strcmp(tok, "lw")) t.lw = v;
+        else if (!std::strcmp(tok, "ch")) t.ch = v;
+        else if (!std::strcmp(tok, "bch")) t.bch = v;
+        else if (!std::strcmp(tok, "u")) t.u = v;
+        else if (!std::strcmp(tok, "nt")) t.nt = v;
+    }
+    return t;
+}
+
+static int32_t pow2_floor(int64_t x) {
+    int32_t p = 1;
+    while ((int64_t)p * 2 <= x) p *= 2;
+    return p;
+}
+
+PlanParams choose_params(int32_t m, int64_t nnz, int32_t n, const Tuning &t) {
+    (void)m;
+    PlanParams p;
+    p.BN = 128;
+    p.ALPHA = 4;
+    p.LW = 32;
+    // Enough independent wavefront tasks to fill 256 CUs several times over, but pieces long
+    // enough that the per-piece overhead stays small.
+    const int64_t coltiles = std::max<int64_t>(1, (n + 511) / 512);
+    p.CH = std::min<int32_t>(1024, std::max<int32_t>(128, pow2_floor(std::max<int64_t>(1, nnz * coltiles / 32768))));
+    p.U = 8;
+    p.NT = 1;
+    if (t.bn > 0) p.BN = t.bn;
+    if (t.alpha > 0) p.ALPHA = t.alpha;
+    if (t.lw > 0) p.LW = t.lw;
+    if (t.ch > 0) p.CH = t.ch;
+    p.BCH = 4 * p.CH;
+    if (t.bch > 0) p.BCH = t.bch;
+    if (t.u > 0) p.U = t.u;
+    if (t.nt >= 0) p.NT = t.nt;
+    // Hard limits the kernels rely on.
+    p.BN = std::min(std::max(p.BN, 16), kBNMax);
+    p.LW = std::min(std::max(p.LW, 0), kLWMax);
+    p.ALPHA = std::max(p.ALPHA, (p.BN + kWindowRowsMax - 1) / kWindowRowsMax);  // <= 64 rows per window
+    p.CH = std::max(p.CH, p.LW);
+    p.BCH = std::max(p.BCH, 64);
+    p.U = p.U >= 8 ? 8 : 4;
+    p.NT &= 3;
+    return p;
+}
+
+static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
+
+WorkspaceLayout layout_workspace(int32_t m, int64_t nnz, int32_t n, const PlanParams &p) {
+    WorkspaceLayout L{};
+    L.nblk = ((int64_t)m + kBlock - 1) / kBlock;
+    L.n_windows = (nnz + (int64_t)p.ALPHA * m) / p.BN + 1;
+    L.cap_wave = std::min<int64_t>(m, nnz / (p.LW + 1));
+    const int64_t long_rows = std::min<int64_t>(m, nnz / ((int64_t)p.CH + 1));
+    L.cap_items = nnz / p.BCH + long_rows;
+    L.cap_split = std::min<int64_t>(m, nnz / ((int64_t)p.BCH + 1));
+    L.cap_slots = nnz / p.BCH + L.cap_split;
+    L.partial_stride = (n + 3) / 4 * 4;
+    uint64_t off = 0;
+    L.off_counts = off;
+    off = align_up(off + (uint64_t)kQ * L.nblk * 4, 256);
+    L.off_totals = off;
+    off = align_up(off + kQ * 4, 256);
+    L.off_win = off;
+    off = align_up(off + (uint64_t)(L.n_windows + 1) * 4, 256);
+    L.off_wave = off;
+    off = align_up(off + (uint64_t)L.cap_wave * 4, 256);
+    L.off_items = off;
+    off = align_up(off + (uint64_t)L.cap_items * 16, 256);
+    L.off_split = off;
+    off = align_up(off + (uint64_t)L.cap_split * 16, 256);
+    L.off_partials = off;
+    off = align_up(off + (uint64_t)L.cap_slots * L.partial_stride * 4, 256);
+    L.total = std::max<uint64_t>(off, 256);
+    return L;
+}
+
+scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, hipStream_t stream) {
+    const WorkspaceLayout &L = plan->layout;
+    char *ws = plan->workspace;
+    int32_t totals[kQ] = {0, 0, 0, 0, 0};
+    if (plan->m > 0) {
+        PlanArgs a{};
+        a.rowptr = rowptr;
+        a.m = plan->m;
+        a.LW = plan->params.LW;
+        a.CH = plan->params.CH;
+        a.BCH = plan->params.BCH;
+        a.nblk = L.nblk;
+        a.counts = reinterpret_cast<int32_t *>(ws + L.off_counts);
+        a.totals = reinterpret_cast<int32_t *>(ws + L.off_totals);
+        a.wave_rows = reinterpret_cast<int32_t *>(ws + L.off_wave);
+        a.items = reinterpret_cast<int4 *>(ws + L.off_items);
+        a.split = reinterpret_cast<int4 *>(ws + L.off_split);
+        a.cap_wave = L.cap_wave;
+        a.cap_items = L.cap_items;
+        a.cap_split = L.cap_split;
+        hipLaunchKernelGGL(plan_count_kernel, dim3((uint32_t)L.nblk), dim3(kBlock), 0, stream, a);
+        hipLaunchKernelGGL(plan_scan_kernel, dim3(1), dim3(1024), 0, stream, a);
+        hipLaunchKernelGGL(plan_scatter_kernel, dim3((uint32_t)L.nblk), dim3(kBlock), 0, stream, a);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "launch plan kernels");
+        e = hipMemcpyAsync(totals, a.totals, sizeof(totals), hipMemcpyDeviceToHost, stream);
+        if (e != hipSuccess) return hip_fail(e, "copy plan totals");
+    }
+    {
+        // also for m == 0: the window table then reads [0, 0]
+        const int64_t wblocks = (L.n_windows + 1 + kBlock - 1) / kBlock;
+        hipLaunchKernelGGL(plan_window_kernel, dim3((uint32_t)wblocks), dim3(kBlock), 0, stream, rowptr, plan->m,
+                           plan->params.BN, plan->params.ALPHA, L.n_windows,
+                           reinterpret_cast<int32_t *>(ws + L.off_win));
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "launch plan_window_kernel");
+        e = hipStreamSynchronize(stream);
+        if (e != hipSuccess) return hip_fail(e, "wait for plan kernels");
+    }
+    plan->n_wave = totals[0];
+    plan->n_items = totals[1];
+    plan->n_split = totals[2];
+    plan->n_slots = totals[3];
+    plan->n_short = totals[4];
+    if (plan->n_wave > L.cap_wave || plan->n_items > L.cap_items || plan->n_split > L.cap_split ||
+        plan->n_slots > L.cap_slots) {
+        set_error("plan lists exceed the workspace bound (rowptr changed or is not non-decreasing?)");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    return SCORCH_OK;
+}
+
+}  // namespace scorch

@@ -1,0 +1,199 @@
+"""GPU parity: the HIP path (through the C ABI) against the fp64 CPU oracle, element by element.
+
+Bar: bit-exact on small-integer inputs; |C - C_ref| <= 1e-5 * (|A|.|B|)_ij + 1e-7 on fp32 inputs.
+"""
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_16883_amd as sp
+from oracle import plan_oracle
+from workloads import (csr_from_row_lengths, integer_valued, make_scaled_config, with_padding)
+
+from gpu_util import DeviceProblem, check_against_oracle, read_plan_arrays, tuning
+
+pytestmark = pytest.mark.gpu
+
+# (config, scale): sizes the oracle finishes in well under a second, still many tiles and a ragged tail
+SMALL = [(1, 1.0), (2, 0.12), (3, 0.08), (4, 0.006), (5, 0.06)]
+# parameter sets that force every execution path (windows, wave rows, single- and multi-piece block rows)
+TUNES = [None, "bn=64,alpha=2,lw=8,ch=32,bch=64,u=4,nt=0", "bn=256,lw=64,ch=256,bch=256,u=8,nt=3",
+         "bn=128,lw=0,ch=64,bch=128", "bn=32,alpha=1,lw=64,ch=64,bch=1000000"]
+
+
+def run_both(p, ldc=None, exact=False, label=""):
+    d = DeviceProblem(p, ldc=ldc)
+    plan = d.make_plan()
+    worst = check_against_oracle(p, d.run_planned(plan), d.ldc, exact=exact, label=label + " planned")
+    check_against_oracle(p, d.run_natural(), d.ldc, exact=exact, label=label + " plan-free")
+    plan.destroy()
+    return worst
+
+
+@pytest.mark.parametrize("cfg,scale", SMALL)
+def test_small_configs_fp32_tolerance(cfg, scale):
+    p = make_scaled_config(cfg, scale, seed=0)
+    print(f"cfg {cfg} x{scale}: m={p.m} k={p.k} n={p.n} nnz={p.nnz} maxrow={p.row_lengths.max()}", flush=True)
+    run_both(p, label=p.name)
+
+
+@pytest.mark.parametrize("cfg,scale", SMALL)
+def test_small_configs_integer_bit_exact(cfg, scale):
+    p = integer_valued(make_scaled_config(cfg, scale, seed=1), seed=1)
+    run_both(p, exact=True, label=p.name)
+
+
+@pytest.mark.parametrize("tune", TUNES)
+@pytest.mark.parametrize("cfg,scale", [(3, 0.08), (4, 0.006), (1, 1.0)])
+def test_every_path_under_forced_parameters(cfg, scale, tune):
+    with tuning(tune):
+        p = make_scaled_config(cfg, scale, seed=2)
+        run_both(p, label=f"{p.name} [{tune}]")
+        run_both(integer_valued(p, seed=2), exact=True, label=f"{p.name} int [{tune}]")
+
+
+@pytest.mark.parametrize("n", [1, 2, 3, 4, 5, 17, 63, 64, 65, 100, 128, 130, 255, 256, 257, 300, 512, 516, 1000])
+def test_column_counts(n):
+    rng = np.random.default_rng(n)
+    lens = np.concatenate([rng.integers(0, 40, size=150), [700, 0, 300, 65, 64, 33, 32, 1]])
+    p = csr_from_row_lengths(lens, 500, n, seed=n, duplicates=True)
+    with tuning("ch=128,bch=256"):
+        run_both(p, label=f"n={n}")
+        run_both(integer_valued(p, seed=n), exact=True, label=f"n={n} int")
+
+
+@pytest.mark.parametrize("n,ldb,ldc", [(64, 80, 72), (100, 101, 100), (100, 104, 108), (7, 9, 8), (128, 130, 131), (256, 260, 264)])
+def test_leading_dimensions_and_padding(n, ldb, ldc):
+    rng = np.random.default_rng(7)
+    p = csr_from_row_lengths(rng.integers(0, 90, size=300), 400, n, seed=3)
+    p = with_padding(p, ldb)  # B padding holds NaN: reading it into a result would show
+    run_both(p, ldc=ldc, label=f"n={n} ldb={ldb} ldc={ldc}")
+    run_both(integer_valued(p, seed=4), ldc=ldc, exact=True, label=f"n={n} ldb={ldb} ldc={ldc} int")
+
+
+def test_unaligned_base_pointers_fall_back_to_narrow_loads():
+    p = csr_from_row_lengths(np.random.default_rng(1).integers(0, 50, size=200), 300, 64, seed=5)
+    d = DeviceProblem(p)
+    # shift B and C by one float: 4-byte aligned only
+    Bbuf = torch.empty(p.k * p.n + 1, dtype=torch.float32, device=d.dev)
+    Bv = Bbuf[1:].view(p.k, p.n)
+    Bv.copy_(d.B)
+    Cbuf = torch.full((p.m * p.n + 1,), -7.0, dtype=torch.float32, device=d.dev)
+    Cv = Cbuf[1:].view(p.m, p.n)
+    plan = d.make_plan()
+    sp.scorch_spmm_csr_planned(plan, d.rowptr, d.colidx, d.vals, Bv, Cv)
+    torch.cuda.synchronize()
+    check_against_oracle(p, Cv.cpu().numpy(), p.n, label="unaligned planned")
+    Cv.fill_(-7.0)
+    sp.scorch_spmm_csr(p.m, p.k, p.n, d.rowptr, d.colidx, d.vals, Bv, Cv)
+    torch.cuda.synchronize()
+    check_against_oracle(p, Cv.cpu().numpy(), p.n, label="unaligned plan-free")
+    assert float(Cbuf[0]) == -7.0
+    plan.destroy()
+
+
+EDGE_LENS = {
+    "m1": [5], "m1_empty": [0], "all_empty": [0] * 777, "last_empty": [3, 9, 0], "first_heavy": [5000, 1, 2, 0, 3],
+    "only_heavy": [20000], "many_empty_then_row": [0] * 300 + [400] + [0] * 300, "len_boundaries": [31, 32, 33, 63, 64, 65, 127, 128, 129, 511, 512, 513, 2047, 2048, 2049],
+    "alternating": [0, 1] * 200,
+}
+
+
+@pytest.mark.parametrize("name", sorted(EDGE_LENS))
+def test_edge_shapes(name):
+    lens = EDGE_LENS[name]
+    for n, k in ((128, 3000), (100, 1), (4, 37)):
+        p = csr_from_row_lengths(lens, k, n, seed=11, duplicates=True, sorted_cols=False)
+        run_both(p, label=f"{name} n={n} k={k}")
+        run_both(integer_valued(p, seed=12), exact=True, label=f"{name} n={n} k={k} int")
+
+
+def test_single_row_with_very_many_entries():
+    # integer case: |partial sums| <= 4*8*500000 = 1.6e7 < 2^24, so every summation order is exact
+    p = integer_valued(csr_from_row_lengths([500_000, 2, 0], 50_000, 128, seed=13, duplicates=True), seed=13)
+    run_both(p, exact=True, label="5e5-entry row int")
+    q = csr_from_row_lengths([1_000_000, 2, 0], 50_000, 128, seed=14, duplicates=True)
+    run_both(q, label="1e6-entry row fp32")
+
+
+def test_zero_sizes_and_argument_errors():
+    dev = torch.device("cuda:0")
+    z32 = torch.zeros(1, dtype=torch.int32, device=dev)
+    f = torch.zeros((4, 4), dtype=torch.float32, device=dev)
+    sp.scorch_spmm_csr(0, 4, 4, z32, z32, f.view(-1), f, f)  # m = 0: no work
+    sp.scorch_spmm_csr(4, 4, 0, torch.zeros(5, dtype=torch.int32, device=dev), z32, f.view(-1), f[:, :0], f[:, :0])
+    plan = sp.scorch_spmm_plan(0, 4, 4, z32, 0)
+    sp.scorch_spmm_csr_planned(plan, z32, z32, f.view(-1), f, f)
+    plan.destroy()
+    lib = sp.load_library()
+    rp = torch.zeros(5, dtype=torch.int32, device=dev)
+    # ldb < n and ldc < n are rejected before anything is enqueued
+    st = lib.scorch_spmm_csr(4, 4, 4, rp.data_ptr(), z32.data_ptr(), f.data_ptr(), f.data_ptr(), 3, f.data_ptr(), 4, None)
+    assert st == sp.binding.SCORCH_ERR_INVALID_ARG
+    st = lib.scorch_spmm_csr(4, 4, 4, rp.data_ptr(), z32.data_ptr(), f.data_ptr(), f.data_ptr(), 4, f.data_ptr(), 2, None)
+    assert st == sp.binding.SCORCH_ERR_INVALID_ARG
+    st = lib.scorch_spmm_csr(-1, 4, 4, rp.data_ptr(), z32.data_ptr(), f.data_ptr(), f.data_ptr(), 4, f.data_ptr(), 4, None)
+    assert st == sp.binding.SCORCH_ERR_INVALID_ARG
+    st = lib.scorch_spmm_csr(4, 4, 4, None, z32.data_ptr(), f.data_ptr(), f.data_ptr(), 4, f.data_ptr(), 4, None)
+    assert st == sp.binding.SCORCH_ERR_INVALID_ARG and b"NULL" in lib.scorch_last_error()
+    # workspace too small / misaligned
+    ws = torch.empty(512, dtype=torch.uint8, device=dev)
+    with pytest.raises(sp.ScorchError) as e:
+        sp.scorch_spmm_plan(100000, 4, 4, torch.zeros(100001, dtype=torch.int32, device=dev), 0, workspace=ws)
+    assert e.value.status == sp.binding.SCORCH_ERR_WORKSPACE_TOO_SMALL
+    with pytest.raises(sp.ScorchError) as e:
+        sp.scorch_spmm_plan(4, 4, 4, rp, 0, workspace=torch.empty(4096, dtype=torch.uint8, device=dev)[1:])
+    assert e.value.status == sp.binding.SCORCH_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("tune", TUNES)
+@pytest.mark.parametrize("cfg,scale", [(3, 0.08), (4, 0.006), (2, 0.12)])
+def test_plan_lists_match_the_plan_oracle_bit_for_bit(cfg, scale, tune):
+    with tuning(tune):
+        p = make_scaled_config(cfg, scale, seed=3)
+        d = DeviceProblem(p)
+        plan = d.make_plan()
+        info, got = read_plan_arrays(plan)
+        want = plan_oracle(p.rowptr, info.BN, info.ALPHA, info.LW, info.CH, info.BCH)
+        assert info.nnz == p.nnz and info.n_short_rows == int(want["n_short"])
+        assert info.n_partial_slots == int(want["n_slots"])
+        for key in ("win_row_start", "wave_rows", "items", "split"):
+            assert got[key].shape == want[key].shape, key
+            assert np.array_equal(got[key], want[key]), key
+        plan.destroy()
+
+
+def test_plan_edge_patterns_match_oracle():
+    for lens in ([0] * 1000, [100000], [0, 0, 5000, 0], [33] * 600, []):
+        p = csr_from_row_lengths(lens, 4000, 8, seed=1, duplicates=True)
+        with tuning("bn=64,alpha=2,lw=16,ch=64,bch=128"):
+            d = DeviceProblem(p)
+            plan = d.make_plan()
+            info, got = read_plan_arrays(plan)
+            want = plan_oracle(p.rowptr, info.BN, info.ALPHA, info.LW, info.CH, info.BCH)
+            for key in ("win_row_start", "wave_rows", "items", "split"):
+                assert np.array_equal(got[key], want[key]), (key, lens[:4])
+            plan.destroy()
+
+
+def test_repeated_runs_are_bit_identical():
+    p = make_scaled_config(3, 0.08, seed=5)
+    d = DeviceProblem(p)
+    plan = d.make_plan()
+    first = d.run_planned(plan).copy()
+    for _ in range(3):
+        assert np.array_equal(first, d.run_planned(plan))
+    plan.destroy()
+
+
+def test_runs_on_a_side_stream():
+    p = make_scaled_config(1, 1.0, seed=6)
+    d = DeviceProblem(p)
+    s = torch.cuda.Stream()
+    plan = sp.scorch_spmm_plan(p.m, p.k, p.n, d.rowptr, p.nnz, stream=s)
+    d.reset_C()
+    torch.cuda.synchronize()
+    sp.scorch_spmm_csr_planned(plan, d.rowptr, d.colidx, d.vals, d._B_arg(), d._C_arg(), stream=s)
+    s.synchronize()
+    check_against_oracle(p, d.Cfull.cpu().numpy(), d.ldc, label="side stream")
+    plan.destroy()
