@@ -133,6 +133,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other four workloads")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run one plain 1 GiB device copy (known traffic) so that a counter run can scale FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. "
@@ -178,6 +180,12 @@ def main():
             f"{out['gbs_min_traffic']:.0f} GB/s min-traffic = {100 * out['frac_hbm']:.1f}% of HBM peak  (plan {res.plan_ms:.2f} ms)")
         return res, out
 
+    if args.calibrate_copy:
+        src = flush_buf
+        dst = torch.empty_like(src)
+        dst.copy_(src)  # 1 GiB read + 1 GiB written by one elementwise copy kernel
+        torch.cuda.synchronize()
+        del dst
     res, head = run_config(args.config, args.steps, args.warmup, cold_steps=5)
     name = CONFIG_NAMES[args.config]
     tr = traffic.get(name)
