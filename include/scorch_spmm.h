@@ -65,11 +65,12 @@ scorch_status_t scorch_spmm_csr(int32_t m, int32_t k, int32_t n,
                                 void *stream);
 
 /*
- * Upper bound, in bytes, of the device workspace a plan for (m, nnz, n) needs.  The bound
- * depends on the tuning read from the environment (see scorch_spmm_plan); call both with the
- * same environment.  Host-only; touches no device.
+ * Size, in bytes, of the device workspace a plan for an m x k matrix with nnz stored entries and
+ * n dense columns needs (row lists, partial rows, and for some shapes a repacked copy of B).
+ * It depends on the tuning read from the environment (see scorch_spmm_plan); call both with
+ * the same environment.  Host-only; touches no device.
  */
-scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int64_t nnz, int32_t n, size_t *bytes_out);
+scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n, int64_t nnz, size_t *bytes_out);
 
 /*
  * One-time analysis of a sparsity pattern (the paper names load balance and irregular access
@@ -97,7 +98,9 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
 
 /*
  * Planned SpMM: same result contract as scorch_spmm_csr, executed through the plan's row lists
- * (one fused launch, plus one small fix-up launch when rows were split across workgroups).
+ * (one fused launch, plus one small fix-up launch when rows were split across workgroups, plus,
+ * for wide B with few rows, a pre-pass that copies B into column-slice-major order so that each
+ * accelerator die keeps its slice of B in its own L2).
  * Never waits, never allocates.  The partial rows live in the plan workspace, so two
  * executions of one plan must not overlap in time (same stream, or synchronise).
  */

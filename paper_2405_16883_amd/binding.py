@@ -63,7 +63,7 @@ def load_library() -> ctypes.CDLL:
     lib.scorch_spmm_csr.restype = i32
     lib.scorch_spmm_csr.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp]
     lib.scorch_spmm_plan_workspace_bytes.restype = i32
-    lib.scorch_spmm_plan_workspace_bytes.argtypes = [i32, i64, i32, ctypes.POINTER(ctypes.c_size_t)]
+    lib.scorch_spmm_plan_workspace_bytes.argtypes = [i32, i32, i32, i64, ctypes.POINTER(ctypes.c_size_t)]
     lib.scorch_spmm_plan.restype = i32
     lib.scorch_spmm_plan.argtypes = [i32, i32, i32, vp, vp, vp, ctypes.c_size_t, vp, ctypes.POINTER(vp)]
     lib.scorch_spmm_csr_planned.restype = i32
@@ -116,10 +116,10 @@ def scorch_spmm_csr(m: int, k: int, n: int, rowptr: torch.Tensor, colidx: torch.
                                _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))
 
 
-def scorch_spmm_plan_workspace_bytes(m: int, nnz: int, n: int) -> int:
+def scorch_spmm_plan_workspace_bytes(m: int, k: int, n: int, nnz: int) -> int:
     lib = load_library()
     out = ctypes.c_size_t(0)
-    _check(lib.scorch_spmm_plan_workspace_bytes(m, nnz, n, ctypes.byref(out)))
+    _check(lib.scorch_spmm_plan_workspace_bytes(m, k, n, nnz, ctypes.byref(out)))
     return int(out.value)
 
 
@@ -159,7 +159,7 @@ def scorch_spmm_plan(m: int, k: int, n: int, rowptr: torch.Tensor, nnz: int,
     """Analyse the pattern behind ``rowptr``.  ``workspace`` (uint8, GPU) is allocated with torch if not given."""
     lib = load_library()
     if workspace is None:
-        workspace = torch.empty(scorch_spmm_plan_workspace_bytes(m, nnz, n), dtype=torch.uint8, device=rowptr.device)
+        workspace = torch.empty(scorch_spmm_plan_workspace_bytes(m, k, n, nnz), dtype=torch.uint8, device=rowptr.device)
     handle = ctypes.c_void_p(0)
     _check(lib.scorch_spmm_plan(m, k, n, _dev_ptr(rowptr, torch.int32, "rowptr"), None,
                                 _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),

@@ -52,12 +52,12 @@ scorch_status_t scorch_spmm_csr(int32_t m, int32_t k, int32_t n, const int32_t *
     scorch_status_t st = check_operands(m, k, n, rowptr, colidx, vals, B, ldb, C, ldc);
     if (st != SCORCH_OK || m == 0 || n == 0) return st;
     const Tuning t = read_tuning_from_env();
-    const PlanParams p = choose_params(m, 0, n, t);
+    const PlanParams p = choose_params(m, k, 0, n, t);
     return launch_natural(m, n, rowptr, colidx, vals, B, ldb, C, ldc, p.U, p.NT, static_cast<hipStream_t>(stream));
 }
 
-scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int64_t nnz, int32_t n, size_t *bytes_out) {
-    if (!bytes_out || m < 0 || n < 0 || nnz < 0) {
+scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n, int64_t nnz, size_t *bytes_out) {
+    if (!bytes_out || m < 0 || k < 0 || n < 0 || nnz < 0) {
         set_error("workspace_bytes: bad argument");
         return SCORCH_ERR_INVALID_ARG;
     }
@@ -65,8 +65,8 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int64_t nnz, int32_t
         set_error("nnz = %lld does not fit int32 indices", (long long)nnz);
         return SCORCH_ERR_UNSUPPORTED;
     }
-    const PlanParams p = choose_params(m, nnz, n, read_tuning_from_env());
-    *bytes_out = (size_t)layout_workspace(m, nnz, n, p).total;
+    const PlanParams p = choose_params(m, k, nnz, n, read_tuning_from_env());
+    *bytes_out = (size_t)layout_workspace(m, k, nnz, n, p).total;
     return SCORCH_OK;
 }
 
@@ -108,8 +108,8 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n, const int32_t 
     plan->k = k;
     plan->n = n;
     plan->nnz = nnz32;
-    plan->params = choose_params(m, nnz32, n, read_tuning_from_env());
-    plan->layout = layout_workspace(m, nnz32, n, plan->params);
+    plan->params = choose_params(m, k, nnz32, n, read_tuning_from_env());
+    plan->layout = layout_workspace(m, k, nnz32, n, plan->params);
     plan->workspace = static_cast<char *>(workspace);
     if (hipGetDevice(&plan->device) != hipSuccess) plan->device = -1;
     if (workspace_bytes < plan->layout.total) {

@@ -16,6 +16,8 @@
 // No MFMA: the work is a gather, not a dense contraction.  No atomics: summation order is fixed.
 #include "spmm_internal.h"
 
+#include <algorithm>
+
 namespace scorch {
 
 template <int V> struct Vec;
@@ -148,6 +150,35 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
     }
 }
 
+// Which column tile and which unit of row work a workgroup owns.
+//
+// Default: tile-major (all row work of column tile 0, then tile 1, ...).
+// XCD-sliced (a.xcd_slices > 0): workgroups are dealt to the 8 XCDs round-robin by index, and each
+// XCD has its own L2.  Every XCD is therefore given its own narrow column slices of B, one after the
+// other, so that the slice it is gathering from stays resident in that XCD's L2.  With fewer than 8
+// slices, 8/slots XCDs share a slice and split the row work between them.  The mapping only steers
+// locality; any assignment of workgroups to XCDs gives the same result.
+__device__ __forceinline__ bool tile_of_workgroup(const ExecArgs &a, uint32_t per_tile, uint32_t &ct, uint32_t &b) {
+    if (a.xcd_slices == 0) {
+        ct = blockIdx.x / per_tile;
+        b = blockIdx.x - ct * per_tile;
+        return true;
+    }
+    const uint32_t xcd = blockIdx.x & (kXcds - 1);
+    const uint32_t q = blockIdx.x / kXcds;
+    if (a.xcd_slices >= kXcds) {
+        const uint32_t ls = q / per_tile;
+        b = q - ls * per_tile;
+        ct = xcd + kXcds * ls;
+        return ct < (uint32_t)a.ncoltiles;
+    }
+    const uint32_t slots = (uint32_t)a.xcd_slices;  // 1, 2 or 4 slots; slot >= ncoltiles stays idle
+    const uint32_t share = kXcds / slots;
+    ct = xcd % slots;
+    b = q * share + xcd / slots;
+    return ct < (uint32_t)a.ncoltiles && b < per_tile;
+}
+
 constexpr int smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
 
 template <int V, int G, int T, int U, int NT>
@@ -169,14 +200,15 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     const int lig = lane % G;
 
     const uint32_t per_tile = (uint32_t)a.nb_items + (uint32_t)a.nb_wave + (uint32_t)a.nb_win;
-    const uint32_t ct = blockIdx.x / per_tile;
-    const uint32_t b = blockIdx.x - ct * per_tile;
+    uint32_t ct, b;
+    if (!tile_of_workgroup(a, per_tile, ct, b)) return;
 
     const int c0 = (int)ct * TW + lig * V;
     bool colok[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) colok[t] = (c0 + t * GV) < a.n;
-    const float *Bc = a.B + c0;
+    // packed B (XCD-sliced mode with a repacked copy): slice ct is a dense k x 32 block
+    const float *Bc = a.b_tile_stride ? a.B + (int64_t)ct * a.b_tile_stride + lig * V : a.B + c0;
 
     int *lcol = s_raw + wv * smem_ints_per_wave();
     float *lval = reinterpret_cast<float *>(lcol + kStageMax);
@@ -320,6 +352,23 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     }
 }
 
+// Copies B (k x n, row stride ldb) into slice-major order: slice s is a dense k x 32 block holding
+// columns [32 s, 32 s + 32).  A column slice of a row-major B with a large power-of-two row stride
+// lands in few L2 sets; the dense copy makes a slice a contiguous range that an XCD's L2 keeps.
+__global__ __launch_bounds__(kBlock) void spmm_pack_b_kernel(const float *B, int64_t ldb, int32_t k, int32_t n,
+                                                             float *Bp) {
+    typedef float f4 __attribute__((ext_vector_type(4)));
+    const int quads = (n + 3) / 4;  // n % 4 == 0 is guaranteed by the caller
+    const int64_t total = (int64_t)k * quads;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < total; i += (int64_t)gridDim.x * kBlock) {
+        const int64_t r = i / quads;
+        const int c = (int)(i - r * quads) * 4;
+        const f4 v = *reinterpret_cast<const f4 *>(B + r * ldb + c);
+        const int s = c / kSliceCols;
+        *reinterpret_cast<f4 *>(Bp + ((int64_t)s * k + r) * kSliceCols + (c - s * kSliceCols)) = v;
+    }
+}
+
 // Rows cut into several pieces: add the partial rows in piece order.
 __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const FixupArgs a) {
     const int s = blockIdx.x;
@@ -339,14 +388,26 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const FixupArgs a) {
 // ------------------------------------------------------------------------------------------
 struct Mapping {
     int V, G, T, ncoltiles;
+    int xcd_slices;  // 0: tile-major grid; else number of slice slots dealt over the XCDs
 };
 
-static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc) {
-    Mapping mp;
+static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc, bool sliced) {
+    Mapping mp{};
     const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(C);
     if (n % 4 == 0 && ldb % 4 == 0 && ldc % 4 == 0 && pb % 16 == 0 && pc % 16 == 0) mp.V = 4;
     else if (n % 2 == 0 && ldb % 2 == 0 && ldc % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) mp.V = 2;
     else mp.V = 1;
+    mp.xcd_slices = 0;
+    if (sliced && mp.V == 4) {
+        // 32-column (one 128-byte line) slices of B, one slice per XCD at a time
+        mp.G = kSliceCols / 4;
+        mp.T = 1;
+        mp.ncoltiles = (n + kSliceCols - 1) / kSliceCols;
+        int slots = 1;
+        while (slots < mp.ncoltiles && slots < kXcds) slots <<= 1;
+        mp.xcd_slices = mp.ncoltiles >= kXcds ? mp.ncoltiles : slots;
+        return mp;
+    }
     const int lanes = (n + mp.V - 1) / mp.V;
     if (lanes <= kWave) {
         int g = 4;
@@ -356,11 +417,19 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
         mp.ncoltiles = 1;
     } else {
         mp.G = kWave;
-        mp.T = lanes > kWave ? 2 : 1;
+        mp.T = 2;
         const int tw = mp.G * mp.V * mp.T;
         mp.ncoltiles = (n + tw - 1) / tw;
     }
     return mp;
+}
+
+// Number of workgroups for `per_tile` units of row work per column tile under the mapping.
+static int64_t grid_size(const Mapping &mp, int64_t per_tile) {
+    if (mp.xcd_slices == 0) return per_tile * mp.ncoltiles;
+    if (mp.xcd_slices >= kXcds) return (int64_t)kXcds * per_tile * ((mp.ncoltiles + kXcds - 1) / kXcds);
+    const int64_t share = kXcds / mp.xcd_slices;
+    return (int64_t)kXcds * ((per_tile + share - 1) / share);
 }
 
 typedef void (*kernel_fn)(const ExecArgs);
@@ -398,7 +467,7 @@ static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b;
 scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                hipStream_t stream) {
-    const Mapping mp = pick_mapping(plan->n, B, ldb, C, ldc);
+    const Mapping mp = pick_mapping(plan->n, B, ldb, C, ldc, plan->params.SLICED != 0);
     ExecArgs a{};
     a.rowptr = rowptr;
     a.colidx = colidx;
@@ -423,11 +492,23 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     a.partial_stride = plan->layout.partial_stride;
     a.LW = plan->params.LW;
     a.ncoltiles = mp.ncoltiles;
+    a.xcd_slices = mp.xcd_slices;
     const int64_t per_tile = (int64_t)a.nb_items + a.nb_wave + a.nb_win;
-    const int64_t grid = per_tile * mp.ncoltiles;
+    const int64_t grid = grid_size(mp, per_tile);
     if (grid > 0x7fffffffLL) {
         set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);
         return SCORCH_ERR_UNSUPPORTED;
+    }
+    if (grid > 0 && mp.xcd_slices != 0 && plan->params.PACK && plan->k > 0) {
+        float *Bp = reinterpret_cast<float *>(ws + plan->layout.off_bpack);
+        const int64_t quads = (int64_t)plan->k * (plan->n / 4);
+        const uint32_t pgrid = (uint32_t)std::min<int64_t>((quads + kBlock - 1) / kBlock, 256 * 32);
+        hipLaunchKernelGGL(spmm_pack_b_kernel, dim3(pgrid), dim3(kBlock), 0, stream, B, ldb, plan->k, plan->n, Bp);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "launch spmm_pack_b_kernel");
+        a.B = Bp;
+        a.ldb = kSliceCols;
+        a.b_tile_stride = (int64_t)plan->k * kSliceCols;
     }
     if (grid > 0) {
         kernel_fn fn = pick_fused(mp.V, mp.G, mp.T, plan->params.U, plan->params.NT);
@@ -454,7 +535,7 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
 scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                int32_t U, int32_t NT, hipStream_t stream) {
-    const Mapping mp = pick_mapping(n, B, ldb, C, ldc);
+    const Mapping mp = pick_mapping(n, B, ldb, C, ldc, false);
     ExecArgs a{};
     a.rowptr = rowptr;
     a.colidx = colidx;

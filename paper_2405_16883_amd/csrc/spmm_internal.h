@@ -17,6 +17,9 @@ constexpr int kBNMax = 256;
 constexpr int kLWMax = 64;
 constexpr int kStageMax = kBNMax + kLWMax;
 constexpr int kWindowRowsMax = 64;  // one lane per row when reading rowptr
+constexpr int kXcds = 8;        // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
+constexpr int kSliceCols = 32;  // XCD-sliced mode: 32 fp32 columns = one 128-byte line of a B row
+constexpr int64_t kL2SliceBudget = 2560 * 1024;  // bytes of B an XCD's 4 MB L2 is trusted to keep resident
 
 // Parameters that decide how rows are classed and cut (paper has none of this; see the header).
 struct PlanParams {
@@ -27,21 +30,23 @@ struct PlanParams {
     int32_t BCH;    // block rows: pieces of at most BCH entries
     int32_t U;      // gathers in flight per lane group (4 or 8)
     int32_t NT;     // bit 0: streaming stores for C; bit 1: streaming loads for colidx/vals
+    int32_t SLICED; // 1: the workload suits XCD-sliced execution (see want_sliced)
+    int32_t PACK;   // 1: sliced execution gathers from a slice-major copy of B made at every call
 };
 
 struct Tuning {
-    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1;
+    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1;
 };
 Tuning read_tuning_from_env();
-PlanParams choose_params(int32_t m, int64_t nnz, int32_t n, const Tuning &t);
+PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t);
 
 struct WorkspaceLayout {
-    uint64_t off_counts, off_totals, off_win, off_wave, off_items, off_split, off_partials, total;
+    uint64_t off_counts, off_totals, off_win, off_wave, off_items, off_split, off_partials, off_bpack, total;
     int64_t n_windows, nblk;
     int64_t cap_wave, cap_items, cap_split, cap_slots;
     int32_t partial_stride;
 };
-WorkspaceLayout layout_workspace(int32_t m, int64_t nnz, int32_t n, const PlanParams &p);
+WorkspaceLayout layout_workspace(int32_t m, int32_t k, int64_t nnz, int32_t n, const PlanParams &p);
 
 // Everything the execution kernels need, passed by value.
 struct ExecArgs {
@@ -61,6 +66,8 @@ struct ExecArgs {
     int32_t partial_stride;
     int32_t LW;
     int32_t ncoltiles;
+    int32_t xcd_slices;  // 0 = tile-major grid, else XCD-sliced (see tile_of_workgroup)
+    int64_t b_tile_stride;  // 0: B is the caller's row-major matrix; else B is slice-major, floats per slice
 };
 
 struct FixupArgs {

@@ -190,6 +190,8 @@ Tuning read_tuning_from_env() {
         else if (!std::strcmp(tok, "bch")) t.bch = v;
         else if (!std::strcmp(tok, "u")) t.u = v;
         else if (!std::strcmp(tok, "nt")) t.nt = v;
+        else if (!std::strcmp(tok, "sliced")) t.sliced = v;
+        else if (!std::strcmp(tok, "pack")) t.pack = v;
     }
     return t;
 }
@@ -200,16 +202,32 @@ static int32_t pow2_floor(int64_t x) {
     return p;
 }
 
-PlanParams choose_params(int32_t m, int64_t nnz, int32_t n, const Tuning &t) {
-    (void)m;
+// XCD-sliced execution pays when B as a whole overflows an XCD's L2 but a 128-byte-wide column
+// slice of it fits, and rows are long enough that re-reading colidx/vals once per slice is cheap
+// next to the gathers (8 bytes of A against 128 bytes of B per entry and slice).
+static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
+    if (m <= 0 || n % 4 != 0 || n < 2 * kSliceCols) return false;
+    const int64_t slice_bytes = (int64_t)k * kSliceCols * 4;
+    const int64_t b_bytes = (int64_t)k * n * 4;
+    return slice_bytes <= kL2SliceBudget && b_bytes > kL2SliceBudget && nnz / m >= 32;
+}
+
+PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t) {
     PlanParams p;
     p.BN = 128;
     p.ALPHA = 4;
     p.LW = 32;
+    p.SLICED = want_sliced(m, k, nnz, n) ? 1 : 0;
+    if (t.sliced >= 0) p.SLICED = t.sliced != 0 && n % 4 == 0;
+    // A row stride of B above 512 bytes scatters a 128-byte column slice over few L2 sets; gather from a
+    // dense slice-major copy instead (costs one read and one write of B per call).
+    p.PACK = (p.SLICED && n > 128) ? 1 : 0;
+    if (t.pack >= 0) p.PACK = (p.SLICED && t.pack != 0) ? 1 : 0;
     // Enough independent wavefront tasks to fill 256 CUs several times over, but pieces long
     // enough that the per-piece overhead stays small.
-    const int64_t coltiles = std::max<int64_t>(1, (n + 511) / 512);
-    p.CH = std::min<int32_t>(1024, std::max<int32_t>(128, pow2_floor(std::max<int64_t>(1, nnz * coltiles / 32768))));
+    const int64_t coltiles = p.SLICED ? (n + kSliceCols - 1) / kSliceCols : std::max<int64_t>(1, (n + 511) / 512);
+    const int32_t ch_cap = p.SLICED ? 4096 : 1024;
+    p.CH = std::min<int32_t>(ch_cap, std::max<int32_t>(128, pow2_floor(std::max<int64_t>(1, nnz * coltiles / 32768))));
     p.U = 8;
     p.NT = 1;
     if (t.bn > 0) p.BN = t.bn;
@@ -233,7 +251,7 @@ PlanParams choose_params(int32_t m, int64_t nnz, int32_t n, const Tuning &t) {
 
 static uint64_t align_up(uint64_t x, uint64_t a) { return (x + a - 1) / a * a; }
 
-WorkspaceLayout layout_workspace(int32_t m, int64_t nnz, int32_t n, const PlanParams &p) {
+WorkspaceLayout layout_workspace(int32_t m, int32_t k, int64_t nnz, int32_t n, const PlanParams &p) {
     WorkspaceLayout L{};
     L.nblk = ((int64_t)m + kBlock - 1) / kBlock;
     L.n_windows = (nnz + (int64_t)p.ALPHA * m) / p.BN + 1;
@@ -258,6 +276,8 @@ WorkspaceLayout layout_workspace(int32_t m, int64_t nnz, int32_t n, const PlanPa
     off = align_up(off + (uint64_t)L.cap_split * 16, 256);
     L.off_partials = off;
     off = align_up(off + (uint64_t)L.cap_slots * L.partial_stride * 4, 256);
+    L.off_bpack = off;
+    if (p.PACK) off = align_up(off + (uint64_t)k * ((n + kSliceCols - 1) / kSliceCols) * kSliceCols * 4, 256);
     L.total = std::max<uint64_t>(off, 256);
     return L;
 }

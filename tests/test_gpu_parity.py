@@ -92,6 +92,19 @@ def test_unaligned_base_pointers_fall_back_to_narrow_loads():
     plan.destroy()
 
 
+@pytest.mark.parametrize("n", [64, 96, 128, 160, 256, 288, 544, 1024])
+def test_xcd_sliced_column_mapping(n):
+    """Forces the XCD-sliced grid (32-column slices dealt over the 8 XCDs) on shapes with 2..32 slices."""
+    rng = np.random.default_rng(n)
+    lens = np.concatenate([rng.integers(0, 70, size=400), [900, 0, 300, 2100, 64, 33, 32, 1]])
+    p = csr_from_row_lengths(lens, 700, n, seed=n + 1, duplicates=True)
+    for tune in ("sliced=1,pack=0", "sliced=1,pack=1", "sliced=1,pack=1,ch=128,bch=256,lw=8"):
+        with tuning(tune):
+            run_both(p, label=f"sliced n={n} [{tune}]")
+            run_both(integer_valued(p, seed=n), exact=True, label=f"sliced n={n} int [{tune}]")
+            run_both(with_padding(p, n + 4), ldc=n + 8, label=f"sliced n={n} padded [{tune}]")
+
+
 EDGE_LENS = {
     "m1": [5], "m1_empty": [0], "all_empty": [0] * 777, "last_empty": [3, 9, 0], "first_heavy": [5000, 1, 2, 0, 3],
     "only_heavy": [20000], "many_empty_then_row": [0] * 300 + [400] + [0] * 300, "len_boundaries": [31, 32, 33, 63, 64, 65, 127, 128, 129, 511, 512, 513, 2047, 2048, 2049],

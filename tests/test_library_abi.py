@@ -31,14 +31,14 @@ def test_host_only_calls(repo_root):
     assert lib.scorch_status_string(0) == b"ok"
     assert lib.scorch_status_string(-3) == b"workspace too small"
     # workspace bound: host arithmetic only, grows with nnz, rejects nnz >= 2^31
-    a = sp.scorch_spmm_plan_workspace_bytes(1000, 10_000, 128)
-    b = sp.scorch_spmm_plan_workspace_bytes(1000, 10_000_000, 128)
+    a = sp.scorch_spmm_plan_workspace_bytes(1000, 1000, 128, 10_000)
+    b = sp.scorch_spmm_plan_workspace_bytes(1000, 1000, 128, 10_000_000)
     assert 0 < a < b
     with pytest.raises(sp.ScorchError) as e:
-        sp.scorch_spmm_plan_workspace_bytes(10, 2**31, 4)
+        sp.scorch_spmm_plan_workspace_bytes(10, 10, 4, 2**31)
     assert e.value.status == sp.binding.SCORCH_ERR_UNSUPPORTED
     with pytest.raises(sp.ScorchError) as e:
-        sp.scorch_spmm_plan_workspace_bytes(-1, 5, 4)
+        sp.scorch_spmm_plan_workspace_bytes(-1, 5, 4, 5)
     assert e.value.status == sp.binding.SCORCH_ERR_INVALID_ARG
 
 
