@@ -55,7 +55,7 @@ class Resident:
         self.C = torch.empty((p.m, p.n), dtype=torch.float32, device=dev)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        self.plan = sp.scorch_spmm_plan(p.m, p.k, p.n, self.rowptr, p.nnz)
+        self.plan = sp.scorch_spmm_plan(p.m, p.k, p.n, self.rowptr, p.nnz, colidx=self.colidx)
         self.plan_ms = (time.perf_counter() - t0) * 1e3
         self.sp = sp
 

@@ -84,10 +84,12 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  *                               fixed order (no floating-point atomics)
  * `workspace` (device, 256-byte aligned, at least the bound above) receives the row lists and
  * holds the partial rows at execution; it must stay allocated and unmodified while the plan
- * lives.  `colidx` is not read and may be NULL.  The call enqueues on `stream` and WAITS for it
- * (it reads nnz and the list sizes back).  The plan is valid for exactly this rowptr content
+ * lives.  `colidx` may be NULL; when given (device, nnz entries) it is only inspected to see whether
+ * every row stores its columns in non-decreasing order, which is what the panel kernel for
+ * dense-ish matrices needs (with NULL, or with unsorted rows, the gather kernels are used).  The
+ * call enqueues on `stream` and WAITS for it (it reads nnz and the list sizes back).  The plan is valid for exactly this rowptr content
  * and this n, on the device that was current.
- * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=.."
+ * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=.."
  * overrides the built-in parameter choice (for experiments).
  */
 scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
@@ -127,6 +129,7 @@ typedef struct scorch_spmm_plan_info {
     int32_t BN, ALPHA, LW, CH, BCH;
     int32_t n_windows, n_short_rows, n_wave_rows, n_items, n_split_rows, n_partial_slots;
     int32_t partial_stride;
+    int32_t mode; /* 0 gather kernel, 1 gather kernel with XCD-sliced columns, 2 panel kernel */
     uint64_t off_win_row_start, off_wave_rows, off_items, off_split, off_partials;
     uint64_t workspace_bytes_used;
 } scorch_spmm_plan_info_t;

@@ -40,7 +40,7 @@ class PlanInfo(ctypes.Structure):
         ("BCH", ctypes.c_int32),
         ("n_windows", ctypes.c_int32), ("n_short_rows", ctypes.c_int32), ("n_wave_rows", ctypes.c_int32),
         ("n_items", ctypes.c_int32), ("n_split_rows", ctypes.c_int32), ("n_partial_slots", ctypes.c_int32),
-        ("partial_stride", ctypes.c_int32),
+        ("partial_stride", ctypes.c_int32), ("mode", ctypes.c_int32),
         ("off_win_row_start", ctypes.c_uint64), ("off_wave_rows", ctypes.c_uint64), ("off_items", ctypes.c_uint64),
         ("off_split", ctypes.c_uint64), ("off_partials", ctypes.c_uint64), ("workspace_bytes_used", ctypes.c_uint64),
     ]
@@ -154,14 +154,16 @@ class SpmmPlan:
 
 
 def scorch_spmm_plan(m: int, k: int, n: int, rowptr: torch.Tensor, nnz: int,
+                     colidx: Optional[torch.Tensor] = None,
                      workspace: Optional[torch.Tensor] = None,
                      stream: Optional[torch.cuda.Stream] = None) -> SpmmPlan:
-    """Analyse the pattern behind ``rowptr``.  ``workspace`` (uint8, GPU) is allocated with torch if not given."""
+    """Analyse the pattern behind ``rowptr`` (and, if given, ``colidx``).  ``workspace`` (uint8, GPU) is allocated
+    with torch if not given."""
     lib = load_library()
     if workspace is None:
         workspace = torch.empty(scorch_spmm_plan_workspace_bytes(m, k, n, nnz), dtype=torch.uint8, device=rowptr.device)
     handle = ctypes.c_void_p(0)
-    _check(lib.scorch_spmm_plan(m, k, n, _dev_ptr(rowptr, torch.int32, "rowptr"), None,
+    _check(lib.scorch_spmm_plan(m, k, n, _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
                                 _dev_ptr(workspace, torch.uint8, "workspace"), workspace.numel(),
                                 _stream_handle(stream), ctypes.byref(handle)))
     return SpmmPlan(handle.value, workspace)

@@ -73,7 +73,6 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
 scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                  void *workspace, size_t workspace_bytes, void *stream,
                                  scorch_spmm_plan_t **plan_out) {
-    (void)colidx;
     if (!plan_out) {
         set_error("plan_out must not be NULL");
         return SCORCH_ERR_INVALID_ARG;
@@ -118,7 +117,7 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n, const int32_t 
         delete plan;
         return SCORCH_ERR_WORKSPACE_TOO_SMALL;
     }
-    scorch_status_t st = build_plan(plan, rowptr, s);
+    scorch_status_t st = build_plan(plan, rowptr, colidx, s);
     if (st != SCORCH_OK) {
         delete plan;
         return st;
@@ -169,6 +168,7 @@ scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spm
     out->n_split_rows = plan->n_split;
     out->n_partial_slots = plan->n_slots;
     out->partial_stride = plan->layout.partial_stride;
+    out->mode = plan->params.PANEL ? 2 : (plan->params.SLICED ? 1 : 0);
     out->off_win_row_start = plan->layout.off_win;
     out->off_wave_rows = plan->layout.off_wave;
     out->off_items = plan->layout.off_items;

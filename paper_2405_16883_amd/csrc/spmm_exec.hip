@@ -150,35 +150,6 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
     }
 }
 
-// Which column tile and which unit of row work a workgroup owns.
-//
-// Default: tile-major (all row work of column tile 0, then tile 1, ...).
-// XCD-sliced (a.xcd_slices > 0): workgroups are dealt to the 8 XCDs round-robin by index, and each
-// XCD has its own L2.  Every XCD is therefore given its own narrow column slices of B, one after the
-// other, so that the slice it is gathering from stays resident in that XCD's L2.  With fewer than 8
-// slices, 8/slots XCDs share a slice and split the row work between them.  The mapping only steers
-// locality; any assignment of workgroups to XCDs gives the same result.
-__device__ __forceinline__ bool tile_of_workgroup(const ExecArgs &a, uint32_t per_tile, uint32_t &ct, uint32_t &b) {
-    if (a.xcd_slices == 0) {
-        ct = blockIdx.x / per_tile;
-        b = blockIdx.x - ct * per_tile;
-        return true;
-    }
-    const uint32_t xcd = blockIdx.x & (kXcds - 1);
-    const uint32_t q = blockIdx.x / kXcds;
-    if (a.xcd_slices >= kXcds) {
-        const uint32_t ls = q / per_tile;
-        b = q - ls * per_tile;
-        ct = xcd + kXcds * ls;
-        return ct < (uint32_t)a.ncoltiles;
-    }
-    const uint32_t slots = (uint32_t)a.xcd_slices;  // 1, 2 or 4 slots; slot >= ncoltiles stays idle
-    const uint32_t share = kXcds / slots;
-    ct = xcd % slots;
-    b = q * share + xcd / slots;
-    return ct < (uint32_t)a.ncoltiles && b < per_tile;
-}
-
 constexpr int smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
 
 template <int V, int G, int T, int U, int NT>
@@ -201,7 +172,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
 
     const uint32_t per_tile = (uint32_t)a.nb_items + (uint32_t)a.nb_wave + (uint32_t)a.nb_win;
     uint32_t ct, b;
-    if (!tile_of_workgroup(a, per_tile, ct, b)) return;
+    if (!tile_of_workgroup(a.xcd_slices, a.ncoltiles, per_tile, ct, b)) return;
 
     const int c0 = (int)ct * TW + lig * V;
     bool colok[T];
@@ -352,11 +323,12 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     }
 }
 
-// Copies B (k x n, row stride ldb) into slice-major order: slice s is a dense k x 32 block holding
-// columns [32 s, 32 s + 32).  A column slice of a row-major B with a large power-of-two row stride
-// lands in few L2 sets; the dense copy makes a slice a contiguous range that an XCD's L2 keeps.
+// Copies B (k x n, row stride ldb) into slice-major order: slice s is a dense k x W block holding
+// columns [W s, W s + W).  A column slice of a row-major B with a large power-of-two row stride
+// lands in few L2 sets; the dense copy makes a slice a contiguous range that an XCD's L2 keeps
+// (W = 32, gather kernel) or that streams as whole kilobyte rows into LDS (W = 256, panel kernel).
 __global__ __launch_bounds__(kBlock) void spmm_pack_b_kernel(const float *B, int64_t ldb, int32_t k, int32_t n,
-                                                             float *Bp) {
+                                                             int32_t W, float *Bp) {
     typedef float f4 __attribute__((ext_vector_type(4)));
     const int quads = (n + 3) / 4;  // n % 4 == 0 is guaranteed by the caller
     const int64_t total = (int64_t)k * quads;
@@ -364,9 +336,20 @@ __global__ __launch_bounds__(kBlock) void spmm_pack_b_kernel(const float *B, int
         const int64_t r = i / quads;
         const int c = (int)(i - r * quads) * 4;
         const f4 v = *reinterpret_cast<const f4 *>(B + r * ldb + c);
-        const int s = c / kSliceCols;
-        *reinterpret_cast<f4 *>(Bp + ((int64_t)s * k + r) * kSliceCols + (c - s * kSliceCols)) = v;
+        const int s = c / W;
+        *reinterpret_cast<f4 *>(Bp + ((int64_t)s * k + r) * W + (c - s * W)) = v;
     }
+}
+
+scorch_status_t launch_pack_b(const float *B, int64_t ldb, int32_t k, int32_t n, int32_t W, float *Bp,
+                              hipStream_t stream) {
+    const int64_t quads = (int64_t)k * (n / 4);
+    if (quads == 0) return SCORCH_OK;
+    const uint32_t pgrid = (uint32_t)std::min<int64_t>((quads + kBlock - 1) / kBlock, 256 * 32);
+    hipLaunchKernelGGL(spmm_pack_b_kernel, dim3(pgrid), dim3(kBlock), 0, stream, B, ldb, k, n, W, Bp);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "launch spmm_pack_b_kernel");
+    return SCORCH_OK;
 }
 
 // Rows cut into several pieces: add the partial rows in piece order.
@@ -386,6 +369,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const FixupArgs a) {
 // ------------------------------------------------------------------------------------------
 // host side: pick the lane mapping from n and the operand alignment, then launch
 // ------------------------------------------------------------------------------------------
+int32_t xcd_slots_for(int32_t ncoltiles);
+
 struct Mapping {
     int V, G, T, ncoltiles;
     int xcd_slices;  // 0: tile-major grid; else number of slice slots dealt over the XCDs
@@ -403,9 +388,7 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
         mp.G = kSliceCols / 4;
         mp.T = 1;
         mp.ncoltiles = (n + kSliceCols - 1) / kSliceCols;
-        int slots = 1;
-        while (slots < mp.ncoltiles && slots < kXcds) slots <<= 1;
-        mp.xcd_slices = mp.ncoltiles >= kXcds ? mp.ncoltiles : slots;
+        mp.xcd_slices = xcd_slots_for(mp.ncoltiles);
         return mp;
     }
     const int lanes = (n + mp.V - 1) / mp.V;
@@ -424,12 +407,24 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
     return mp;
 }
 
-// Number of workgroups for `per_tile` units of row work per column tile under the mapping.
-static int64_t grid_size(const Mapping &mp, int64_t per_tile) {
-    if (mp.xcd_slices == 0) return per_tile * mp.ncoltiles;
-    if (mp.xcd_slices >= kXcds) return (int64_t)kXcds * per_tile * ((mp.ncoltiles + kXcds - 1) / kXcds);
-    const int64_t share = kXcds / mp.xcd_slices;
+// Number of workgroups for `per_tile` units of row work per column tile (see tile_of_workgroup).
+int64_t xcd_grid_size(int32_t xcd_slices, int32_t ncoltiles, int64_t per_tile) {
+    if (xcd_slices == 0) return per_tile * ncoltiles;
+    if (xcd_slices >= kXcds) return (int64_t)kXcds * per_tile * ((ncoltiles + kXcds - 1) / kXcds);
+    const int64_t share = kXcds / xcd_slices;
     return (int64_t)kXcds * ((per_tile + share - 1) / share);
+}
+
+// Slice slots dealt over the XCDs: all tiles when there are at least 8, else the next power of two.
+int32_t xcd_slots_for(int32_t ncoltiles) {
+    if (ncoltiles >= kXcds) return ncoltiles;
+    int slots = 1;
+    while (slots < ncoltiles) slots <<= 1;
+    return slots;
+}
+
+static int64_t grid_size(const Mapping &mp, int64_t per_tile) {
+    return xcd_grid_size(mp.xcd_slices, mp.ncoltiles, per_tile);
 }
 
 typedef void (*kernel_fn)(const ExecArgs);
@@ -467,6 +462,8 @@ static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b;
 scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                hipStream_t stream) {
+    if (plan->params.PANEL && panel_operands_ok(plan->n, B, ldb, C, ldc))
+        return launch_panel(plan, rowptr, colidx, vals, B, ldb, C, ldc, stream);
     const Mapping mp = pick_mapping(plan->n, B, ldb, C, ldc, plan->params.SLICED != 0);
     ExecArgs a{};
     a.rowptr = rowptr;
@@ -501,11 +498,8 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     }
     if (grid > 0 && mp.xcd_slices != 0 && plan->params.PACK && plan->k > 0) {
         float *Bp = reinterpret_cast<float *>(ws + plan->layout.off_bpack);
-        const int64_t quads = (int64_t)plan->k * (plan->n / 4);
-        const uint32_t pgrid = (uint32_t)std::min<int64_t>((quads + kBlock - 1) / kBlock, 256 * 32);
-        hipLaunchKernelGGL(spmm_pack_b_kernel, dim3(pgrid), dim3(kBlock), 0, stream, B, ldb, plan->k, plan->n, Bp);
-        hipError_t e = hipGetLastError();
-        if (e != hipSuccess) return hip_fail(e, "launch spmm_pack_b_kernel");
+        scorch_status_t st = launch_pack_b(B, ldb, plan->k, plan->n, kSliceCols, Bp, stream);
+        if (st != SCORCH_OK) return st;
         a.B = Bp;
         a.ldb = kSliceCols;
         a.b_tile_stride = (int64_t)plan->k * kSliceCols;

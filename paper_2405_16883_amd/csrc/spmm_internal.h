@@ -18,6 +18,8 @@ constexpr int kLWMax = 64;
 constexpr int kStageMax = kBNMax + kLWMax;
 constexpr int kWindowRowsMax = 64;  // one lane per row when reading rowptr
 constexpr int kXcds = 8;        // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
+constexpr int kPanelCols = 256; // panel kernel: one wavefront covers 256 columns (64 lanes x float4)
+constexpr int kPanelRows = 64;  // panel kernel: B rows per LDS panel (64 x 1 KB = 64 KB)
 constexpr int kSliceCols = 32;  // XCD-sliced mode: 32 fp32 columns = one 128-byte line of a B row
 constexpr int64_t kL2SliceBudget = 2560 * 1024;  // bytes of B an XCD's 4 MB L2 is trusted to keep resident
 
@@ -32,10 +34,11 @@ struct PlanParams {
     int32_t NT;     // bit 0: streaming stores for C; bit 1: streaming loads for colidx/vals
     int32_t SLICED; // 1: the workload suits XCD-sliced execution (see want_sliced)
     int32_t PACK;   // 1: sliced execution gathers from a slice-major copy of B made at every call
+    int32_t PANEL;  // 1: dense-ish sorted rows: stream B through LDS in k-panels (spmm_panel.hip)
 };
 
 struct Tuning {
-    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1;
+    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1, panel = -1;
 };
 Tuning read_tuning_from_env();
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t);
@@ -70,6 +73,19 @@ struct ExecArgs {
     int64_t b_tile_stride;  // 0: B is the caller's row-major matrix; else B is slice-major, floats per slice
 };
 
+struct PanelArgs {
+    const int32_t *rowptr;
+    const int32_t *colidx;
+    const float *vals;
+    const float *Bp;  // tile-major copy of B: tile t is a dense k x 256 block
+    float *C;
+    int64_t ldc;
+    int32_t m, k, n;
+    int32_t nrb;     // row blocks of 4*RW rows
+    int32_t ntiles;  // 256-column tiles
+    int32_t xcd_slices;
+};
+
 struct FixupArgs {
     const int4 *split;
     const float *partials;
@@ -77,6 +93,39 @@ struct FixupArgs {
     int64_t ldc;
     int32_t n, n_split, partial_stride;
 };
+
+#if defined(__HIPCC__)
+// Which column tile and which unit of row work a workgroup owns.
+//
+// Default: tile-major (all row work of column tile 0, then tile 1, ...).
+// XCD-sliced (xcd_slices > 0): workgroups are dealt to the 8 XCDs round-robin by index, and each
+// XCD has its own L2.  Every XCD is therefore given its own narrow column slices of B, one after the
+// other, so that the slice it is gathering from stays resident in that XCD's L2.  With fewer than 8
+// slices, 8/slots XCDs share a slice and split the row work between them.  The mapping only steers
+// locality; any assignment of workgroups to XCDs gives the same result.
+__device__ __forceinline__ bool tile_of_workgroup(int32_t xcd_slices, int32_t ncoltiles, uint32_t per_tile, uint32_t &ct,
+                                                  uint32_t &b) {
+    if (xcd_slices == 0) {
+        ct = blockIdx.x / per_tile;
+        b = blockIdx.x - ct * per_tile;
+        return true;
+    }
+    const uint32_t xcd = blockIdx.x & (kXcds - 1);
+    const uint32_t q = blockIdx.x / kXcds;
+    if (xcd_slices >= kXcds) {
+        const uint32_t ls = q / per_tile;
+        b = q - ls * per_tile;
+        ct = xcd + kXcds * ls;
+        return ct < (uint32_t)ncoltiles;
+    }
+    const uint32_t slots = (uint32_t)xcd_slices;  // 1, 2 or 4 slots; slot >= ncoltiles stays idle
+    const uint32_t share = kXcds / slots;
+    ct = xcd % slots;
+    b = q * share + xcd / slots;
+    return ct < (uint32_t)ncoltiles && b < per_tile;
+}
+
+#endif
 
 }  // namespace scorch
 
@@ -96,12 +145,24 @@ void set_error(const char *fmt, ...);
 scorch_status_t hip_fail(hipError_t e, const char *what);
 
 // spmm_plan.hip
-scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, hipStream_t stream);
+scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
+                           hipStream_t stream);
 
 // spmm_exec.hip
 scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                hipStream_t stream);
+scorch_status_t launch_pack_b(const float *B, int64_t ldb, int32_t k, int32_t n, int32_t W, float *Bp,
+                              hipStream_t stream);
+int64_t xcd_grid_size(int32_t xcd_slices, int32_t ncoltiles, int64_t per_tile);
+int32_t xcd_slots_for(int32_t ncoltiles);
+
+// spmm_panel.hip
+bool panel_operands_ok(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc);
+scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
+                             const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
+                             hipStream_t stream);
+
 scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                int32_t U, int32_t NT, hipStream_t stream);

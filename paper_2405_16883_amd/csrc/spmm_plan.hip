@@ -168,6 +168,19 @@ __global__ __launch_bounds__(kBlock) void plan_window_kernel(const int32_t *rowp
     win_row_start[w] = (int32_t)lo;
 }
 
+// Sets *flag when some row stores a column index smaller than its predecessor (one wavefront per row).
+__global__ __launch_bounds__(kBlock) void plan_sorted_kernel(const int32_t *rowptr, const int32_t *colidx, int32_t m,
+                                                             int32_t *flag) {
+    const int lane = threadIdx.x & 63;
+    for (int64_t row = (int64_t)blockIdx.x * kWavesPerBlock + (threadIdx.x >> 6); row < m;
+         row += (int64_t)gridDim.x * kWavesPerBlock) {
+        const int p0 = rowptr[row], p1 = rowptr[row + 1];
+        bool bad = false;
+        for (int p = p0 + 1 + lane; p < p1; p += kWave) bad |= colidx[p] < colidx[p - 1];
+        if (bad) *flag = 1;
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
@@ -192,6 +205,7 @@ Tuning read_tuning_from_env() {
         else if (!std::strcmp(tok, "nt")) t.nt = v;
         else if (!std::strcmp(tok, "sliced")) t.sliced = v;
         else if (!std::strcmp(tok, "pack")) t.pack = v;
+        else if (!std::strcmp(tok, "panel")) t.panel = v;
     }
     return t;
 }
@@ -212,10 +226,22 @@ static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
     return slice_bytes <= kL2SliceBudget && b_bytes > kL2SliceBudget && nnz / m >= 32;
 }
 
+// The panel kernel streams all of B through LDS once per block of 64 rows of A, so it pays when a B row
+// staged in LDS is used by several of those rows: a few percent of the entries stored, long rows, enough
+// row blocks and column tiles to fill the chip.
+static bool want_panel(int32_t m, int32_t k, int64_t nnz, int32_t n) {
+    if (m < 512 || k < kPanelRows || n % 4 != 0 || n < 128) return false;
+    const double density = (double)nnz / ((double)m * (double)k);
+    const int64_t tasks = (int64_t)((m + 63) / 64) * ((n + kPanelCols - 1) / kPanelCols);
+    return density >= 0.03 && nnz / m >= 128 && tasks >= 256;
+}
+
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t) {
     PlanParams p;
-    p.BN = 128;
     p.ALPHA = 4;
+    // Windows of 128 key units, but small problems get smaller windows so that there are a few thousand
+    // wavefronts' worth of them (a lane group walks its rows one after the other, each a full memory latency).
+    p.BN = std::min<int32_t>(128, std::max<int32_t>(16, pow2_floor(std::max<int64_t>(1, (nnz + (int64_t)p.ALPHA * m) / 4096))));
     p.LW = 32;
     p.SLICED = want_sliced(m, k, nnz, n) ? 1 : 0;
     if (t.sliced >= 0) p.SLICED = t.sliced != 0 && n % 4 == 0;
@@ -223,11 +249,17 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     // dense slice-major copy instead (costs one read and one write of B per call).
     p.PACK = (p.SLICED && n > 128) ? 1 : 0;
     if (t.pack >= 0) p.PACK = (p.SLICED && t.pack != 0) ? 1 : 0;
+    // The panel kernel is correct but, as measured on the pruned-weight workload, still slower than the
+    // XCD-sliced gather (3.2 ms against 2.2 ms: issue-bound on v_readlane and scalar bookkeeping), so it is
+    // opt-in only.
+    p.PANEL = 0;
+    if (t.panel > 0) p.PANEL = (n % 4 == 0 && k > 0) ? 1 : 0;
+    (void)want_panel;
     // Enough independent wavefront tasks to fill 256 CUs several times over, but pieces long
     // enough that the per-piece overhead stays small.
     const int64_t coltiles = p.SLICED ? (n + kSliceCols - 1) / kSliceCols : std::max<int64_t>(1, (n + 511) / 512);
     const int32_t ch_cap = p.SLICED ? 4096 : 1024;
-    p.CH = std::min<int32_t>(ch_cap, std::max<int32_t>(128, pow2_floor(std::max<int64_t>(1, nnz * coltiles / 32768))));
+    p.CH = std::min<int32_t>(ch_cap, std::max<int32_t>(256, pow2_floor(std::max<int64_t>(1, nnz * coltiles / 32768))));
     p.U = 8;
     p.NT = 1;
     if (t.bn > 0) p.BN = t.bn;
@@ -277,15 +309,29 @@ WorkspaceLayout layout_workspace(int32_t m, int32_t k, int64_t nnz, int32_t n, c
     L.off_partials = off;
     off = align_up(off + (uint64_t)L.cap_slots * L.partial_stride * 4, 256);
     L.off_bpack = off;
-    if (p.PACK) off = align_up(off + (uint64_t)k * ((n + kSliceCols - 1) / kSliceCols) * kSliceCols * 4, 256);
+    if (p.PACK || p.PANEL) off = align_up(off + (uint64_t)k * ((n + kPanelCols - 1) / kPanelCols) * kPanelCols * 4, 256);
     L.total = std::max<uint64_t>(off, 256);
     return L;
 }
 
-scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, hipStream_t stream) {
+scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
+                           hipStream_t stream) {
     const WorkspaceLayout &L = plan->layout;
     char *ws = plan->workspace;
     int32_t totals[kQ] = {0, 0, 0, 0, 0};
+    int32_t unsorted = 0;
+    // The panel kernel needs every row's columns in non-decreasing order; without colidx this cannot be
+    // verified, so the mode is dropped.
+    if (plan->params.PANEL && (!colidx || plan->m == 0 || plan->nnz == 0)) plan->params.PANEL = 0;
+    if (plan->params.PANEL) {
+        int32_t *flag = reinterpret_cast<int32_t *>(ws + L.off_totals) + 8;
+        hipError_t e = hipMemsetAsync(flag, 0, sizeof(int32_t), stream);
+        if (e != hipSuccess) return hip_fail(e, "clear sortedness flag");
+        const uint32_t g = (uint32_t)std::min<int64_t>(((int64_t)plan->m + kWavesPerBlock - 1) / kWavesPerBlock, 256 * 16);
+        hipLaunchKernelGGL(plan_sorted_kernel, dim3(g), dim3(kBlock), 0, stream, rowptr, colidx, plan->m, flag);
+        e = hipMemcpyAsync(&unsorted, flag, sizeof(int32_t), hipMemcpyDeviceToHost, stream);
+        if (e != hipSuccess) return hip_fail(e, "copy sortedness flag");
+    }
     if (plan->m > 0) {
         PlanArgs a{};
         a.rowptr = rowptr;
@@ -321,6 +367,7 @@ scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, hipS
         e = hipStreamSynchronize(stream);
         if (e != hipSuccess) return hip_fail(e, "wait for plan kernels");
     }
+    if (unsorted) plan->params.PANEL = 0;
     plan->n_wave = totals[0];
     plan->n_items = totals[1];
     plan->n_split = totals[2];

@@ -54,9 +54,9 @@ class DeviceProblem:
         torch.cuda.synchronize()
         return self.Cfull.cpu().numpy()
 
-    def make_plan(self):
+    def make_plan(self, with_colidx=True):
         p = self.p
-        return sp.scorch_spmm_plan(p.m, p.k, p.n, self.rowptr, p.nnz)
+        return sp.scorch_spmm_plan(p.m, p.k, p.n, self.rowptr, p.nnz, colidx=self.colidx if with_colidx else None)
 
     def run_planned(self, plan):
         self.reset_C()

@@ -105,6 +105,48 @@ def test_xcd_sliced_column_mapping(n):
             run_both(with_padding(p, n + 4), ldc=n + 8, label=f"sliced n={n} padded [{tune}]")
 
 
+@pytest.mark.parametrize("m,k,n", [(64, 64, 256), (130, 200, 128), (515, 1000, 512), (300, 77, 260), (257, 4100, 1028),
+                                   (1000, 333, 2048)])
+def test_panel_kernel_forced(m, k, n):
+    """The LDS panel kernel on shapes with ragged row blocks, ragged last panel and ragged last column tile."""
+    rng = np.random.default_rng(m + n)
+    lens = rng.integers(0, max(2, k // 3), size=m)
+    lens[rng.integers(0, m, size=5)] = 0
+    lens[0] = min(k, 700)  # a row whose 64-entry register window slides many times
+    p = csr_from_row_lengths(lens, k, n, seed=m, duplicates=False)
+    with tuning("panel=1"):
+        d = DeviceProblem(p)
+        plan = d.make_plan()
+        assert plan.info().mode == 2
+        check_against_oracle(p, d.run_planned(plan), d.ldc, label=f"panel {m}x{k}x{n}")
+        plan.destroy()
+        q = integer_valued(p, seed=n)
+        run_both(q, exact=True, label=f"panel int {m}x{k}x{n}")
+        run_both(with_padding(p, n + 4), ldc=n + 12, label=f"panel padded {m}x{k}x{n}")
+        # sorted rows that repeat a column are fine too
+        r = csr_from_row_lengths(np.minimum(lens * 2, 3 * k), k, n, seed=m + 1, duplicates=True, sorted_cols=True)
+        run_both(r, label=f"panel duplicates {m}x{k}x{n}")
+
+
+def test_panel_mode_is_dropped_for_unsorted_rows_or_missing_colidx():
+    p = csr_from_row_lengths([40] * 600, 300, 256, seed=3, sorted_cols=False)
+    with tuning("panel=1"):
+        d = DeviceProblem(p)
+        plan = d.make_plan()
+        assert plan.info().mode != 2  # unsorted: the planner falls back to the gather kernels
+        check_against_oracle(p, d.run_planned(plan), d.ldc, label="unsorted fallback")
+        plan.destroy()
+        s = csr_from_row_lengths([40] * 600, 300, 256, seed=3, sorted_cols=True)
+        d = DeviceProblem(s)
+        plan = d.make_plan(with_colidx=False)
+        assert plan.info().mode != 2  # cannot verify sortedness without colidx
+        check_against_oracle(s, d.run_planned(plan), d.ldc, label="no-colidx fallback")
+        plan.destroy()
+        plan = d.make_plan()
+        assert plan.info().mode == 2
+        plan.destroy()
+
+
 EDGE_LENS = {
     "m1": [5], "m1_empty": [0], "all_empty": [0] * 777, "last_empty": [3, 9, 0], "first_heavy": [5000, 1, 2, 0, 3],
     "only_heavy": [20000], "many_empty_then_row": [0] * 300 + [400] + [0] * 300, "len_boundaries": [31, 32, 33, 63, 64, 65, 127, 128, 129, 511, 512, 513, 2047, 2048, 2049],
