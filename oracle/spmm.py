@@ -14,6 +14,7 @@ import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "spmm_oracle.c")
+_SRC2 = os.path.join(_HERE, "sddmm_oracle.c")
 _LIB = os.path.join(_HERE, "libspmm_oracle.so")
 _lib = None
 
@@ -24,10 +25,10 @@ def oracle_lib_path() -> str:
 
 def build_oracle(force: bool = False) -> str:
     """Compile the C oracle with gcc (-O2, strict IEEE: no -ffast-math, no FMA contraction)."""
-    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < max(os.path.getmtime(_SRC), os.path.getmtime(_SRC2)):
         tmp = _LIB + f".tmp{os.getpid()}"
         subprocess.check_call(["gcc", "-O2", "-std=c99", "-ffp-contract=off", "-fPIC", "-shared",
-                               "-o", tmp, _SRC, "-lm"])
+                               "-o", tmp, _SRC, _SRC2, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -40,8 +41,37 @@ def _load():
         lib.spmm_csr_oracle.restype = ctypes.c_int
         lib.spmm_csr_oracle.argtypes = [ctypes.c_int64, ctypes.c_int64] + [ctypes.c_void_p] * 4 + \
             [ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        lib.sddmm_csr_oracle.restype = ctypes.c_int
+        lib.sddmm_csr_oracle.argtypes = [ctypes.c_int64, ctypes.c_int64] + [ctypes.c_void_p] * 4 + \
+            [ctypes.c_int64, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
+
+
+def sddmm_csr_oracle(m: int, d: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray,
+                     B: np.ndarray, Ct: np.ndarray, want_T: bool = True):
+    """D_p = vals[p] * <B[i,:d], Ct[colidx[p],:d]> in fp64 for every stored entry p of row i, and its magnitude sum.
+
+    ``B`` is m x ldb and ``Ct`` (the second factor, transposed) k x ldc, both float32 row-major.
+    """
+    lib = _load()
+    rowptr = np.ascontiguousarray(rowptr, dtype=np.int32)
+    colidx = np.ascontiguousarray(colidx, dtype=np.int32)
+    vals = np.ascontiguousarray(vals, dtype=np.float32)
+    B = np.ascontiguousarray(B, dtype=np.float32)
+    Ct = np.ascontiguousarray(Ct, dtype=np.float32)
+    nnz = int(rowptr[-1])
+    assert rowptr.shape[0] == m + 1 and B.shape[0] >= m and B.shape[1] >= d and Ct.shape[1] >= d
+    if nnz:
+        assert int(colidx[:nnz].min()) >= 0 and int(colidx[:nnz].max()) < Ct.shape[0]
+    D = np.empty(nnz, dtype=np.float64)
+    T = np.empty(nnz, dtype=np.float64) if want_T else None
+    rc = lib.sddmm_csr_oracle(m, d, rowptr.ctypes.data, colidx.ctypes.data, vals.ctypes.data,
+                              B.ctypes.data, B.shape[1], Ct.ctypes.data, Ct.shape[1], D.ctypes.data,
+                              T.ctypes.data if want_T else None)
+    if rc != 0:
+        raise ValueError("sddmm_csr_oracle: malformed CSR")
+    return D, T
 
 
 def spmm_csr_oracle(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, vals: np.ndarray,
