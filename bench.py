@@ -96,6 +96,36 @@ def summarize(p, wall_ms, ev_ms, bytes_min):
     }
 
 
+def time_sddmm(res, torch, sp, d, steps=30, warmup=5):
+    """SDDMM (D = A (.) (B C)) on the resident pattern with random m x d and k x d factors: events per call."""
+    p = res.p
+    g = torch.Generator(device="cuda:0").manual_seed(1)
+    X = torch.randn((p.m, d), generator=g, dtype=torch.float32, device="cuda:0")
+    Yt = torch.randn((p.k, d), generator=g, dtype=torch.float32, device="cuda:0")
+    out = torch.empty(max(p.nnz, 1), dtype=torch.float32, device="cuda:0")
+
+    def call():
+        sp.scorch_sddmm_csr_planned(res.plan, d, res.rowptr, res.colidx, res.vals, X, Yt, out)
+
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    ev = []
+    for _ in range(steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        call()
+        b.record()
+        ev.append((a, b))
+    torch.cuda.synchronize()
+    ms = float(np.mean([a.elapsed_time(b) for a, b in ev]))
+    uniq = int(np.count_nonzero(np.bincount(p.colidx, minlength=p.k))) if p.nnz else 0
+    bytes_min = p.nnz * 12 + (p.m + 1) * 4 + p.m * d * 4 + uniq * d * 4
+    return {"d": d, "event_ms_mean": ms, "gflops": 2.0 * p.nnz * d / (ms * 1e-3) / 1e9,
+            "bytes_min": bytes_min, "gbs_min_traffic": bytes_min / (ms * 1e-3) / 1e9,
+            "frac_hbm": bytes_min / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+
+
 def cpu_baseline_and_check(res, torch, target_nnz=12_000_000):
     """Time the serial fp64 oracle on a contiguous block of rows (~target_nnz entries) and compare the GPU rows."""
     from oracle import spmm_csr_oracle  # the only place the benchmark touches the oracle
@@ -211,9 +241,13 @@ def main():
                 continue
             torch.cuda.empty_cache()
             r, o = run_config(cfg, 50 if cfg != 4 else 20, 5, cold_steps=10 if cfg != 4 else 3)
+            if cfg == 3:
+                o["sddmm"] = time_sddmm(r, torch, sp, 128)
+                log(f"[bench] sddmm on cfg 3 pattern, d=128: {o['sddmm']['event_ms_mean']:.4f} ms  {o['sddmm']['gflops']:.0f} GFLOP/s  "
+                    f"{100 * o['sddmm']['frac_hbm']:.1f}% of HBM peak (min-traffic model)")
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
                                                            "gbs_min_traffic", "frac_hbm", "cold_event_ms_mean",
-                                                           "cold_frac_hbm", "plan_ms")}
+                                                           "cold_frac_hbm", "plan_ms") + (("sddmm",) if "sddmm" in o else ())}
             del r
 
     line = {

@@ -136,6 +136,30 @@ typedef struct scorch_spmm_plan_info {
 
 scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spmm_plan_info_t *out);
 
+/*
+ * SDDMM on the pattern of A (paper, Section 3.1, SDDMM example; Section 5.4):
+ *
+ *        D = A (.) (B C),      D_ij = A_ij * sum_t B_it * C_tj     for every stored (i, j)
+ *
+ * D has the sparsity pattern of A, so only its values are produced: out_vals[p] for the p-th stored
+ * entry (row i, column colidx[p]).  B is m x d (row stride ldb >= d).  The second factor is passed
+ * TRANSPOSED: Ct = C^T is k x d (row stride ldct >= d), so that column j of C is the contiguous row j
+ * of Ct.  d must not exceed 1024 (256 when B or Ct is only 4-byte aligned, 512 for 8-byte alignment);
+ * larger d gives SCORCH_ERR_UNSUPPORTED.  out_vals (float[nnz], device) may be the same array as vals
+ * (in place) and must otherwise not overlap any input.  fp32 products, fp32 accumulation, fixed
+ * summation order.  The planned variant reuses a plan made by scorch_spmm_plan for the same rowptr
+ * (any n); the plan-free variant runs one wavefront per row.
+ */
+scorch_status_t scorch_sddmm_csr(int32_t m, int32_t k, int32_t d,
+                                 const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                                 const float *B, int32_t ldb, const float *Ct, int32_t ldct,
+                                 float *out_vals, void *stream);
+
+scorch_status_t scorch_sddmm_csr_planned(const scorch_spmm_plan_t *plan, int32_t d,
+                                         const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                                         const float *B, int32_t ldb, const float *Ct, int32_t ldct,
+                                         float *out_vals, void *stream);
+
 /* Static text for a status code. */
 const char *scorch_status_string(scorch_status_t status);
 

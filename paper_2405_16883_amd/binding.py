@@ -24,6 +24,7 @@ SCORCH_ERR_HIP = -4
 EXPORTS = (
     "scorch_spmm_csr", "scorch_spmm_plan_workspace_bytes", "scorch_spmm_plan", "scorch_spmm_csr_planned",
     "scorch_spmm_plan_destroy", "scorch_spmm_plan_info", "scorch_status_string", "scorch_last_error",
+    "scorch_sddmm_csr", "scorch_sddmm_csr_planned",
 )
 
 
@@ -72,6 +73,10 @@ def load_library() -> ctypes.CDLL:
     lib.scorch_spmm_plan_destroy.argtypes = [vp]
     lib.scorch_spmm_plan_info.restype = i32
     lib.scorch_spmm_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+    lib.scorch_sddmm_csr.restype = i32
+    lib.scorch_sddmm_csr.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp, vp]
+    lib.scorch_sddmm_csr_planned.restype = i32
+    lib.scorch_sddmm_csr_planned.argtypes = [vp, i32, vp, vp, vp, vp, i32, vp, i32, vp, vp]
     lib.scorch_status_string.restype = ctypes.c_char_p
     lib.scorch_status_string.argtypes = [i32]
     lib.scorch_last_error.restype = ctypes.c_char_p
@@ -176,3 +181,25 @@ def scorch_spmm_csr_planned(plan: SpmmPlan, rowptr: torch.Tensor, colidx: torch.
                                        _dev_ptr(colidx, torch.int32, "colidx"), _dev_ptr(vals, torch.float32, "vals"),
                                        _dev_ptr(B, torch.float32, "B"), _ld(B, "B"),
                                        _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))
+
+
+def scorch_sddmm_csr(m: int, k: int, d: int, rowptr: torch.Tensor, colidx: torch.Tensor, vals: torch.Tensor,
+                     B: torch.Tensor, Ct: torch.Tensor, out_vals: torch.Tensor,
+                     stream: Optional[torch.cuda.Stream] = None) -> None:
+    """out_vals[p] = vals[p] * <B[i, :d], Ct[colidx[p], :d]> through the plan-free entry point."""
+    lib = load_library()
+    _check(lib.scorch_sddmm_csr(m, k, d, _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+                                _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(B, torch.float32, "B"), _ld(B, "B"),
+                                _dev_ptr(Ct, torch.float32, "Ct"), _ld(Ct, "Ct"),
+                                _dev_ptr(out_vals, torch.float32, "out_vals"), _stream_handle(stream)))
+
+
+def scorch_sddmm_csr_planned(plan: SpmmPlan, d: int, rowptr: torch.Tensor, colidx: torch.Tensor, vals: torch.Tensor,
+                             B: torch.Tensor, Ct: torch.Tensor, out_vals: torch.Tensor,
+                             stream: Optional[torch.cuda.Stream] = None) -> None:
+    lib = load_library()
+    _check(lib.scorch_sddmm_csr_planned(plan.handle, d, _dev_ptr(rowptr, torch.int32, "rowptr"),
+                                        _dev_ptr(colidx, torch.int32, "colidx"), _dev_ptr(vals, torch.float32, "vals"),
+                                        _dev_ptr(B, torch.float32, "B"), _ld(B, "B"), _dev_ptr(Ct, torch.float32, "Ct"),
+                                        _ld(Ct, "Ct"), _dev_ptr(out_vals, torch.float32, "out_vals"),
+                                        _stream_handle(stream)))

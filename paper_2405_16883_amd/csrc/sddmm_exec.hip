@@ -1,0 +1,310 @@
+// SDDMM on a CSR pattern for gfx950:  D = A (.) (B C),  D_ij = A_ij * sum_t B_it C_tj  on the stored entries
+// of A (paper, Section 3.1, first example of the programming-model figure; Section 5.4).  The paper's point
+// is fusion: the dense product is never formed, only the sampled dot products are.  Here that is one kernel
+// that, per stored entry, gathers row j of Ct = C^T, multiplies it with the row i of B held in registers and
+// reduces over the lanes.  The row classes, windows and pieces of the SpMM plan are reused unchanged; as no
+// sum runs over the entries of a row, pieces of a long row need no partial rows and no fix-up.
+//
+// Lane mapping as in the SpMM kernels: a group of G lanes covers the d columns (V floats per load, T loads per
+// lane), a wavefront holds S = 64/G groups.  Eight entries are processed per group and step; their eight
+// per-lane partial dot products are reduced with a halving butterfly (4 + 2 + 1 exchanges over lane distances
+// 1, 2, 4 -- DPP and ds_swizzle -- then one exchange per remaining distance), i.e. about one cross-lane
+// operation per entry instead of log2(G).
+#include "device_util.h"
+#include "spmm_internal.h"
+
+namespace scorch {
+
+constexpr int kSddmmBatch = 8;
+
+struct SddmmArgs {
+    const int32_t *rowptr;
+    const int32_t *colidx;
+    const float *vals;
+    const float *B;   // m x d, row stride ldb
+    const float *Ct;  // k x d, row stride ldct
+    float *out;       // nnz
+    int64_t ldb, ldct;
+    int32_t m, d;
+    const int32_t *win_row_start;
+    const int32_t *wave_rows;
+    const int4 *items;
+    int32_t n_windows, n_wave_rows, n_items;
+    int32_t nb_items, nb_wave, nb_win;
+    int32_t LW;
+};
+
+// Sums r[0..7] over the G lanes of a group.  Returns, in every lane, the total of entry
+// u = 4*bit0(lig) + 2*bit1(lig) + bit2(lig) of the batch.
+template <int G> __device__ __forceinline__ float group_reduce8(float (&r)[kSddmmBatch], int lig) {
+    static_assert(G >= 8, "a group must have at least 8 lanes");
+    const bool h1 = (lig & 1) != 0;
+#pragma unroll
+    for (int h = 0; h < 4; ++h) {
+        const float send = h1 ? r[h] : r[h + 4];
+        const float keep = h1 ? r[h + 4] : r[h];
+        r[h] = keep + lane_xor<1>(send);
+    }
+    const bool h2 = (lig & 2) != 0;
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+        const float send = h2 ? r[h] : r[h + 2];
+        const float keep = h2 ? r[h + 2] : r[h];
+        r[h] = keep + lane_xor<2>(send);
+    }
+    const bool h4 = (lig & 4) != 0;
+    float s = (h4 ? r[1] : r[0]) + lane_xor<4>(h4 ? r[0] : r[1]);
+    if constexpr (G > 8) s += lane_xor<8>(s);
+    if constexpr (G > 16) s += lane_xor<16>(s);
+    if constexpr (G > 32) s += lane_xor<32>(s);
+    return s;
+}
+
+// One lane group computes the staged entries e0, e0+es, ... (< e_end) of a row whose B row is in x:
+//   out_base[e] = val[e] * <x, Ct[col[e], :]>
+template <int V, int G, int T>
+__device__ __forceinline__ void sddmm_entries(const typename Vec<V>::type (&x)[T], const int *lcol, const float *lval,
+                                              int e0, int e_end, int es, const float *Yc, int64_t ldct,
+                                              const bool (&colok)[T], int lig, float *out_base) {
+    using vec = typename Vec<V>::type;
+    constexpr int GV = G * V;
+    const int my_u = ((lig & 1) << 2) | (lig & 2) | ((lig & 4) >> 2);
+    for (int e = e0; e < e_end; e += es * kSddmmBatch) {
+        vec y[kSddmmBatch][T];
+#pragma unroll
+        for (int u = 0; u < kSddmmBatch; ++u) {
+            const int ee = e + u * es;
+            const bool ok = ee < e_end;
+            const int c = lcol[ok ? ee : e0];
+            const float *yp = Yc + (int64_t)c * ldct;
+#pragma unroll
+            for (int t = 0; t < T; ++t) y[u][t] = (ok && colok[t]) ? vload<V>(yp + t * GV) : vzero<V>();
+        }
+        float r[kSddmmBatch];
+#pragma unroll
+        for (int u = 0; u < kSddmmBatch; ++u) {
+            float s = 0.f;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if constexpr (V == 1) s = __builtin_fmaf(x[t], y[u][t], s);
+                else
+#pragma unroll
+                    for (int i = 0; i < V; ++i) s = __builtin_fmaf(x[t][i], y[u][t][i], s);
+            }
+            r[u] = s;
+        }
+        const float total = group_reduce8<G>(r, lig);
+        const int ee = e + my_u * es;
+        if (lig < kSddmmBatch && ee < e_end) out_base[ee] = lval[ee] * total;
+    }
+}
+
+// A wavefront walks the entries [pfirst, p1) of one row in chunks of 64 that are `stride` apart.
+template <int V, int G, int T, bool NTA>
+__device__ __forceinline__ void sddmm_row(const typename Vec<V>::type (&x)[T], int *lcol, float *lval, int lane, int grp,
+                                          int lig, int pfirst, int p1, int stride, const SddmmArgs &a, const float *Yc,
+                                          const bool (&colok)[T]) {
+    constexpr int S = kWave / G;
+    int pc = pfirst + lane;
+    int cn = 0;
+    float vn = 0.f;
+    if (pc < p1) {
+        cn = ld_idx<NTA>(a.colidx + pc);
+        vn = ld_val<NTA>(a.vals + pc);
+    }
+    for (int base = pfirst; base < p1; base += stride) {
+        lcol[lane] = cn;
+        lval[lane] = vn;
+        pc = base + stride + lane;
+        if (pc < p1) {
+            cn = ld_idx<NTA>(a.colidx + pc);
+            vn = ld_val<NTA>(a.vals + pc);
+        }
+        wave_lds_sync();
+        const int cnt = min(kWave, p1 - base);
+        sddmm_entries<V, G, T>(x, lcol, lval, grp, cnt, S, Yc, a.ldct, colok, lig, a.out + base);
+        wave_lds_sync();
+    }
+}
+
+template <int V, int T>
+__device__ __forceinline__ void load_x(typename Vec<V>::type (&x)[T], const float *Bc, int GV, const bool (&colok)[T]) {
+#pragma unroll
+    for (int t = 0; t < T; ++t) x[t] = colok[t] ? vload<V>(Bc + t * GV) : vzero<V>();
+}
+
+constexpr int sddmm_smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
+
+template <int V, int G, int T, bool PLANNED>
+__global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
+    using vec = typename Vec<V>::type;
+    constexpr int S = kWave / G;
+    constexpr int GV = G * V;
+    __shared__ int s_raw[kWavesPerBlock * sddmm_smem_ints_per_wave()];
+    const int tid = threadIdx.x;
+    const int wv = tid >> 6;
+    const int lane = tid & 63;
+    const int grp = lane / G;
+    const int lig = lane % G;
+    const int c0 = lig * V;
+    bool colok[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) colok[t] = (c0 + t * GV) < a.d;
+    const float *Yc = a.Ct + c0;
+    int *lcol = s_raw + wv * sddmm_smem_ints_per_wave();
+    float *lval = reinterpret_cast<float *>(lcol + kStageMax);
+    int *lrp = lcol + 2 * kStageMax;
+    vec x[T];
+    const uint32_t b = blockIdx.x;
+
+    if constexpr (!PLANNED) {
+        // plan-free: one wavefront per row in natural order
+        const int64_t row = (int64_t)b * kWavesPerBlock + wv;
+        if (row >= a.m) return;
+        load_x<V, T>(x, a.B + row * a.ldb + c0, GV, colok);
+        sddmm_row<V, G, T, false>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok);
+        return;
+    }
+
+    if (b < (uint32_t)a.nb_items) {
+        // piece of a long row: the 4 wavefronts take interleaved chunks; entries are independent
+        const int4 it = a.items[b];
+        load_x<V, T>(x, a.B + (int64_t)it.x * a.ldb + c0, GV, colok);
+        sddmm_row<V, G, T, false>(x, lcol, lval, lane, grp, lig, it.y + wv * kWave, it.z, kBlock, a, Yc, colok);
+        return;
+    }
+    if (b < (uint32_t)(a.nb_items + a.nb_wave)) {
+        const int idx = (int)(b - a.nb_items) * kWavesPerBlock + wv;
+        if (idx >= a.n_wave_rows) return;
+        const int row = a.wave_rows[idx];
+        load_x<V, T>(x, a.B + (int64_t)row * a.ldb + c0, GV, colok);
+        sddmm_row<V, G, T, false>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok);
+        return;
+    }
+    // window of consecutive short rows: stage the window's entries once, one lane group per row
+    const int w = (int)(b - a.nb_items - a.nb_wave) * kWavesPerBlock + wv;
+    if (w >= a.n_windows) return;
+    const int r0 = a.win_row_start[w];
+    const int r1 = a.win_row_start[w + 1];
+    const int nr = min(r1 - r0, kWindowRowsMax);
+    if (nr <= 0) return;
+    const int rpv = a.rowptr[r0 + min(lane, nr)];
+    const int rlast = a.rowptr[r0 + nr];
+    int rnext = __shfl_down(rpv, 1, kWave);
+    if (lane == kWave - 1) rnext = rlast;
+    const bool is_short = lane < nr && (rnext - rpv) <= a.LW && rnext > rpv;
+    const unsigned long long bal = __ballot(is_short);
+    if (bal == 0ull) return;
+    const int first = __builtin_ctzll(bal);
+    const int last = 63 - __builtin_clzll(bal);
+    const int sbeg = __shfl(rpv, first, kWave);
+    const int send = __shfl(rnext, last, kWave);
+    const int cnt = min(send - sbeg, kStageMax);
+    for (int e = lane; e < cnt; e += kWave) {
+        lcol[e] = a.colidx[sbeg + e];
+        lval[e] = a.vals[sbeg + e];
+    }
+    lrp[lane] = rpv;
+    if (lane == 0) lrp[nr] = rlast;
+    wave_lds_sync();
+    for (int ri = grp; ri < nr; ri += S) {
+        const int q0 = lrp[ri], q1 = lrp[ri + 1];
+        if (q1 - q0 > a.LW || q1 == q0) continue;
+        load_x<V, T>(x, a.B + (int64_t)(r0 + ri) * a.ldb + c0, GV, colok);
+        sddmm_entries<V, G, T>(x, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Yc, a.ldct, colok, lig, a.out + sbeg);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+typedef void (*sddmm_fn)(const SddmmArgs);
+
+template <bool PLANNED> static sddmm_fn pick_sddmm(int V, int G, int T) {
+#define SCORCH_SD(Vv, Gg, Tt) return sddmm_kernel<Vv, Gg, Tt, PLANNED>;
+#define SCORCH_SD_G(Vv)                                   \
+    if (T == 4) { SCORCH_SD(Vv, 64, 4) }                  \
+    if (T == 2) { SCORCH_SD(Vv, 64, 2) }                  \
+    switch (G) {                                          \
+        case 8: SCORCH_SD(Vv, 8, 1)                       \
+        case 16: SCORCH_SD(Vv, 16, 1)                     \
+        case 32: SCORCH_SD(Vv, 32, 1)                     \
+        default: SCORCH_SD(Vv, 64, 1)                     \
+    }
+    switch (V) {
+        case 4: SCORCH_SD_G(4)
+        case 2: SCORCH_SD_G(2)
+        default: SCORCH_SD_G(1)
+    }
+#undef SCORCH_SD_G
+#undef SCORCH_SD
+}
+
+static bool pick_sddmm_mapping(int32_t d, const float *B, int64_t ldb, const float *Ct, int64_t ldct, int &V, int &G,
+                               int &T) {
+    const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(Ct);
+    if (d % 4 == 0 && ldb % 4 == 0 && ldct % 4 == 0 && pb % 16 == 0 && pc % 16 == 0) V = 4;
+    else if (d % 2 == 0 && ldb % 2 == 0 && ldct % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) V = 2;
+    else V = 1;
+    const int lanes = (d + V - 1) / V;
+    T = 1;
+    if (lanes <= kWave) {
+        G = 8;
+        while (G < lanes) G <<= 1;
+    } else {
+        G = kWave;
+        T = lanes <= 2 * kWave ? 2 : 4;
+        if (lanes > 4 * kWave) return false;
+    }
+    return true;
+}
+
+scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t d, const int32_t *rowptr,
+                             const int32_t *colidx, const float *vals, const float *B, int64_t ldb, const float *Ct,
+                             int64_t ldct, float *out, hipStream_t stream) {
+    int V, G, T;
+    if (!pick_sddmm_mapping(d, B, ldb, Ct, ldct, V, G, T)) {
+        set_error("sddmm: d = %d exceeds the %d columns one wavefront covers with this alignment", d, 4 * kWave * V);
+        return SCORCH_ERR_UNSUPPORTED;
+    }
+    SddmmArgs a{};
+    a.rowptr = rowptr;
+    a.colidx = colidx;
+    a.vals = vals;
+    a.B = B;
+    a.Ct = Ct;
+    a.out = out;
+    a.ldb = ldb;
+    a.ldct = ldct;
+    a.m = m;
+    a.d = d;
+    int64_t grid;
+    sddmm_fn fn;
+    if (plan) {
+        char *ws = plan->workspace;
+        a.win_row_start = reinterpret_cast<const int32_t *>(ws + plan->layout.off_win);
+        a.wave_rows = reinterpret_cast<const int32_t *>(ws + plan->layout.off_wave);
+        a.items = reinterpret_cast<const int4 *>(ws + plan->layout.off_items);
+        a.n_windows = (int32_t)plan->layout.n_windows;
+        a.n_wave_rows = plan->n_wave;
+        a.n_items = plan->n_items;
+        a.nb_items = plan->n_items;
+        a.nb_wave = (plan->n_wave + kWavesPerBlock - 1) / kWavesPerBlock;
+        a.nb_win = plan->n_short > 0 ? (int32_t)((plan->layout.n_windows + kWavesPerBlock - 1) / kWavesPerBlock) : 0;
+        a.LW = plan->params.LW;
+        grid = (int64_t)a.nb_items + a.nb_wave + a.nb_win;
+        fn = pick_sddmm<true>(V, G, T);
+    } else {
+        grid = ((int64_t)m + kWavesPerBlock - 1) / kWavesPerBlock;
+        fn = pick_sddmm<false>(V, G, T);
+    }
+    if (grid > 0x7fffffffLL) {
+        set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);
+        return SCORCH_ERR_UNSUPPORTED;
+    }
+    if (grid == 0) return SCORCH_OK;
+    hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return hip_fail(e, "launch sddmm_kernel");
+    return SCORCH_OK;
+}
+
+}  // namespace scorch

@@ -142,6 +142,55 @@ scorch_status_t scorch_spmm_csr_planned(const scorch_spmm_plan_t *plan, const in
     return launch_planned(plan, rowptr, colidx, vals, B, ldb, C, ldc, static_cast<hipStream_t>(stream));
 }
 
+static scorch_status_t check_sddmm(int32_t m, int32_t k, int32_t d, const void *rowptr, const void *B, int64_t ldb,
+                                   const void *Ct, int64_t ldct, const void *out) {
+    if (m < 0 || k < 0 || d < 0) {
+        set_error("sddmm: negative dimension (m=%d k=%d d=%d)", m, k, d);
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    if (m == 0) return SCORCH_OK;
+    if (!rowptr) {
+        set_error("sddmm: rowptr must not be NULL");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    if (ldb < d || ldct < d) {
+        set_error("sddmm: leading dimension smaller than d (ldb=%lld ldct=%lld d=%d)", (long long)ldb, (long long)ldct, d);
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    if (d > 0 && (!B || (k > 0 && !Ct))) {
+        set_error("sddmm: B and Ct must not be NULL");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    (void)out;  // may be NULL only when no entry is stored
+    return SCORCH_OK;
+}
+
+scorch_status_t scorch_sddmm_csr(int32_t m, int32_t k, int32_t d, const int32_t *rowptr, const int32_t *colidx,
+                                 const float *vals, const float *B, int32_t ldb, const float *Ct, int32_t ldct,
+                                 float *out_vals, void *stream) {
+    scorch_status_t st = check_sddmm(m, k, d, rowptr, B, ldb, Ct, ldct, out_vals);
+    if (st != SCORCH_OK || m == 0) return st;
+    return launch_sddmm(nullptr, m, d, rowptr, colidx, vals, B, ldb, Ct, ldct, out_vals,
+                        static_cast<hipStream_t>(stream));
+}
+
+scorch_status_t scorch_sddmm_csr_planned(const scorch_spmm_plan_t *plan, int32_t d, const int32_t *rowptr,
+                                         const int32_t *colidx, const float *vals, const float *B, int32_t ldb,
+                                         const float *Ct, int32_t ldct, float *out_vals, void *stream) {
+    if (!plan) {
+        set_error("plan must not be NULL");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    scorch_status_t st = check_sddmm(plan->m, plan->k, d, rowptr, B, ldb, Ct, ldct, out_vals);
+    if (st != SCORCH_OK || plan->m == 0 || plan->nnz == 0) return st;
+    if (!colidx || !vals || !out_vals) {
+        set_error("sddmm: colidx, vals and out_vals must not be NULL when nnz > 0");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    return launch_sddmm(plan, plan->m, d, rowptr, colidx, vals, B, ldb, Ct, ldct, out_vals,
+                        static_cast<hipStream_t>(stream));
+}
+
 scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan) {
     delete plan;
     return SCORCH_OK;

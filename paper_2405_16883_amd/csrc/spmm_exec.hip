@@ -15,69 +15,11 @@
 //           staged in LDS with coalesced loads, then each group walks one row at a time
 // No MFMA: the work is a gather, not a dense contraction.  No atomics: summation order is fixed.
 #include "spmm_internal.h"
+#include "device_util.h"
 
 #include <algorithm>
 
 namespace scorch {
-
-template <int V> struct Vec;
-template <> struct Vec<1> { using type = float; };
-template <> struct Vec<2> { typedef float type __attribute__((ext_vector_type(2))); };
-template <> struct Vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
-
-template <int V> __device__ __forceinline__ typename Vec<V>::type vzero() {
-    typename Vec<V>::type z;
-    if constexpr (V == 1) z = 0.f;
-    else for (int i = 0; i < V; ++i) z[i] = 0.f;
-    return z;
-}
-template <int V> __device__ __forceinline__ void vfma(typename Vec<V>::type &acc, float a, const typename Vec<V>::type &x) {
-    if constexpr (V == 1) acc = __builtin_fmaf(a, x, acc);
-    else {
-#pragma unroll
-        for (int i = 0; i < V; ++i) acc[i] = __builtin_fmaf(a, x[i], acc[i]);
-    }
-}
-template <int V> __device__ __forceinline__ void vadd(typename Vec<V>::type &acc, const typename Vec<V>::type &x) {
-    if constexpr (V == 1) acc += x;
-    else {
-#pragma unroll
-        for (int i = 0; i < V; ++i) acc[i] += x[i];
-    }
-}
-template <int V> __device__ __forceinline__ typename Vec<V>::type vshfl_xor(const typename Vec<V>::type &x, int off) {
-    typename Vec<V>::type r;
-    if constexpr (V == 1) r = __shfl_xor(x, off, kWave);
-    else {
-#pragma unroll
-        for (int i = 0; i < V; ++i) r[i] = __shfl_xor(x[i], off, kWave);
-    }
-    return r;
-}
-template <int V> __device__ __forceinline__ typename Vec<V>::type vload(const float *p) {
-    return *reinterpret_cast<const typename Vec<V>::type *>(p);
-}
-template <int V, bool NT> __device__ __forceinline__ void vstore(float *p, const typename Vec<V>::type &x) {
-    auto *q = reinterpret_cast<typename Vec<V>::type *>(p);
-    if constexpr (NT) __builtin_nontemporal_store(x, q);
-    else *q = x;
-}
-template <bool NT> __device__ __forceinline__ int ld_idx(const int32_t *p) {
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-template <bool NT> __device__ __forceinline__ float ld_val(const float *p) {
-    if constexpr (NT) return __builtin_nontemporal_load(p);
-    else return *p;
-}
-
-// Orders LDS writes before later LDS reads of other lanes of the same wavefront.  LDS operations
-// of one wavefront execute in program order, so only the compiler has to be held back.
-__device__ __forceinline__ void wave_lds_sync() {
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-    __builtin_amdgcn_wave_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
 
 // One lane group accumulates the staged entries e0, e0+es, ... (< e_end) of a row:
 //   acc[t] += val[e] * B[col[e], c0 + t*G*V .. +V)
@@ -107,15 +49,18 @@ __device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], cons
     }
 }
 
-template <int V, int G, int T>
+// Adds up the S = 64/G lane groups of a wavefront (xor butterfly over the lane distances G..32; DPP,
+// ds_swizzle or ds_bpermute depending on the distance); every lane ends with the full sum.
+template <int V, int G, int T, int OFF = G>
 __device__ __forceinline__ void reduce_groups(typename Vec<V>::type (&acc)[T]) {
-#pragma unroll
-    for (int off = G; off < kWave; off <<= 1)
+    if constexpr (OFF < kWave) {
 #pragma unroll
         for (int t = 0; t < T; ++t) {
-            auto o = vshfl_xor<V>(acc[t], off);
+            auto o = vlane_xor<V, OFF>(acc[t]);
             vadd<V>(acc[t], o);
         }
+        reduce_groups<V, G, T, OFF * 2>(acc);
+    }
 }
 
 // A wavefront walks the entries [p0 + first, p1) of one row in chunks of 64 that are `stride`
