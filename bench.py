@@ -228,7 +228,10 @@ def main():
         "frac": head["frac_hbm"],
         "algorithmic_bytes_per_launch": head["bytes_min"],
         "avg_launch_ms": head["event_ms_mean"],
-        "traffic": tr,
+        "traffic": (tr or {}).get("total_bytes"),
+        "traffic_detail": tr,
+        "frac_of_peak_on_measured_traffic": ((tr["total_bytes"] / (head["event_ms_mean"] * 1e-3) / 1e9 / HBM_PEAK_GBS)
+                                             if tr else None),
     }
     cpu = None if args.no_cpu else cpu_baseline_and_check(res, torch)
     if cpu is not None:

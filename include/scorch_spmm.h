@@ -112,6 +112,26 @@ scorch_status_t scorch_spmm_csr_planned(const scorch_spmm_plan_t *plan,
                                         float *C, int32_t ldc,
                                         void *stream);
 
+/*
+ * Planned SpMM with the epilogue of a GCN-style layer fused into the store of C (paper, Section 5.1:
+ * H' = sigma(A^ H W); evaluated as sigma(A^ (H W) + b), the aggregation comes last and its result is
+ * activated on the way out instead of in a second pass over C):
+ *
+ *        C_ik = act( sum_j A_ij * B_jk + bias_k )
+ *
+ * bias: float[n] on the device, or NULL for no bias.  activation: SCORCH_ACT_IDENTITY or
+ * SCORCH_ACT_RELU.  Everything else as scorch_spmm_csr_planned; with bias == NULL and the identity it
+ * gives bit-identical results to it.  Rows split across workgroups get bias and activation after their
+ * pieces have been added.
+ */
+enum { SCORCH_ACT_IDENTITY = 0, SCORCH_ACT_RELU = 1 };
+scorch_status_t scorch_spmm_csr_planned_epilogue(const scorch_spmm_plan_t *plan,
+                                                 const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                                                 const float *B, int32_t ldb,
+                                                 const float *bias, int32_t activation,
+                                                 float *C, int32_t ldc,
+                                                 void *stream);
+
 /* Frees the host handle only (the workspace belongs to the caller).  NULL is accepted. */
 scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan);
 

@@ -109,3 +109,18 @@ def spmm_csr_oracle(m: int, n: int, rowptr: np.ndarray, colidx: np.ndarray, vals
     if rc != 0:
         raise ValueError("spmm_csr_oracle: malformed CSR or row list")
     return C, T
+
+
+def spmm_bias_act_oracle(m: int, n: int, rowptr, colidx, vals, B, bias, relu: bool, ldb: Optional[int] = None,
+                         rows: Optional[np.ndarray] = None):
+    """GCN-style layer output (paper, Section 5.1: H' = sigma(A^ H W)), evaluated as sigma(A^ (H W) + b):
+    C_ik = act(sum_j A_ij B_jk + bias_k) in fp64, with B standing for H W.  The SpMM part is the plain oracle
+    above; bias and max(., 0) are applied to its fp64 result.  Also returns the magnitude sum T + |bias|."""
+    C, T = spmm_csr_oracle(m, n, rowptr, colidx, vals, B, ldb, rows=rows)
+    if bias is not None:
+        b = np.asarray(bias, dtype=np.float32).astype(np.float64)
+        C = C + b[None, :]
+        T = T + np.abs(b)[None, :]
+    if relu:
+        C = np.maximum(C, 0.0)
+    return C, T

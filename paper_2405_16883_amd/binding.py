@@ -24,7 +24,7 @@ SCORCH_ERR_HIP = -4
 EXPORTS = (
     "scorch_spmm_csr", "scorch_spmm_plan_workspace_bytes", "scorch_spmm_plan", "scorch_spmm_csr_planned",
     "scorch_spmm_plan_destroy", "scorch_spmm_plan_info", "scorch_status_string", "scorch_last_error",
-    "scorch_sddmm_csr", "scorch_sddmm_csr_planned",
+    "scorch_sddmm_csr", "scorch_sddmm_csr_planned", "scorch_spmm_csr_planned_epilogue",
 )
 
 
@@ -73,6 +73,8 @@ def load_library() -> ctypes.CDLL:
     lib.scorch_spmm_plan_destroy.argtypes = [vp]
     lib.scorch_spmm_plan_info.restype = i32
     lib.scorch_spmm_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
+    lib.scorch_spmm_csr_planned_epilogue.restype = i32
+    lib.scorch_spmm_csr_planned_epilogue.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp, i32, vp]
     lib.scorch_sddmm_csr.restype = i32
     lib.scorch_sddmm_csr.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp, vp]
     lib.scorch_sddmm_csr_planned.restype = i32
@@ -203,3 +205,19 @@ def scorch_sddmm_csr_planned(plan: SpmmPlan, d: int, rowptr: torch.Tensor, colid
                                         _dev_ptr(B, torch.float32, "B"), _ld(B, "B"), _dev_ptr(Ct, torch.float32, "Ct"),
                                         _ld(Ct, "Ct"), _dev_ptr(out_vals, torch.float32, "out_vals"),
                                         _stream_handle(stream)))
+
+
+ACT_IDENTITY = 0
+ACT_RELU = 1
+
+
+def scorch_spmm_csr_planned_epilogue(plan: SpmmPlan, rowptr: torch.Tensor, colidx: torch.Tensor, vals: torch.Tensor,
+                                     B: torch.Tensor, bias: Optional[torch.Tensor], activation: int, C: torch.Tensor,
+                                     stream: Optional[torch.cuda.Stream] = None) -> None:
+    """C = act(A @ B + bias) in one pass (bias may be None; activation ACT_IDENTITY or ACT_RELU)."""
+    lib = load_library()
+    _check(lib.scorch_spmm_csr_planned_epilogue(plan.handle, _dev_ptr(rowptr, torch.int32, "rowptr"),
+                                                _dev_ptr(colidx, torch.int32, "colidx"),
+                                                _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(B, torch.float32, "B"),
+                                                _ld(B, "B"), _dev_ptr(bias, torch.float32, "bias"), activation,
+                                                _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))

@@ -60,6 +60,27 @@ template <int V, bool NT> __device__ __forceinline__ void vstore(float *p, const
     if constexpr (NT) __builtin_nontemporal_store(x, q);
     else *q = x;
 }
+// Fused epilogue of a GCN-style layer: v + bias[c..c+V), then the activation (0 identity, 1 ReLU).
+// `bias_c` already points at the lane's first column, or is nullptr.
+template <int V> __device__ __forceinline__ typename Vec<V>::type apply_epilogue(typename Vec<V>::type v, const float *bias_c,
+                                                                              int act) {
+    if (bias_c) {
+        if constexpr (V == 1) v += bias_c[0];
+        else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) v[i] += bias_c[i];
+        }
+    }
+    if (act == 1) {
+        if constexpr (V == 1) v = fmaxf(v, 0.f);
+        else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) v[i] = fmaxf(v[i], 0.f);
+        }
+    }
+    return v;
+}
+
 template <bool NT> __device__ __forceinline__ int ld_idx(const int32_t *p) {
     if constexpr (NT) return __builtin_nontemporal_load(p);
     else return *p;

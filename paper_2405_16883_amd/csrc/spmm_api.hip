@@ -139,7 +139,29 @@ scorch_status_t scorch_spmm_csr_planned(const scorch_spmm_plan_t *plan, const in
         set_error("colidx, vals and B must not be NULL when nnz > 0");
         return SCORCH_ERR_INVALID_ARG;
     }
-    return launch_planned(plan, rowptr, colidx, vals, B, ldb, C, ldc, static_cast<hipStream_t>(stream));
+    return launch_planned(plan, rowptr, colidx, vals, B, ldb, C, ldc, nullptr, 0, static_cast<hipStream_t>(stream));
+}
+
+scorch_status_t scorch_spmm_csr_planned_epilogue(const scorch_spmm_plan_t *plan, const int32_t *rowptr,
+                                                 const int32_t *colidx, const float *vals, const float *B,
+                                                 int32_t ldb, const float *bias, int32_t activation, float *C,
+                                                 int32_t ldc, void *stream) {
+    if (!plan) {
+        set_error("plan must not be NULL");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    if (activation != SCORCH_ACT_IDENTITY && activation != SCORCH_ACT_RELU) {
+        set_error("unknown activation %d", activation);
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    scorch_status_t st = check_operands(plan->m, plan->k, plan->n, rowptr, colidx, vals, B, ldb, C, ldc);
+    if (st != SCORCH_OK || plan->m == 0 || plan->n == 0) return st;
+    if (plan->nnz > 0 && (!colidx || !vals || !B)) {
+        set_error("colidx, vals and B must not be NULL when nnz > 0");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    return launch_planned(plan, rowptr, colidx, vals, B, ldb, C, ldc, bias, activation,
+                          static_cast<hipStream_t>(stream));
 }
 
 static scorch_status_t check_sddmm(int32_t m, int32_t k, int32_t d, const void *rowptr, const void *B, int64_t ldb,

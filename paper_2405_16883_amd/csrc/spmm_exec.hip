@@ -166,6 +166,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
                     if constexpr (V == 1) r = s;
                     else r[i] = s;
                 }
+                // a partial row gets its epilogue in the fix-up, after the pieces are added
+                if (it.w < 0) r = apply_epilogue<V>(r, a.bias ? a.bias + c0 + t * GV : nullptr, a.act);
                 vstore<V, NTC>(dst + t * GV, r);
             }
         }
@@ -185,7 +187,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
             float *dst = a.C + (int64_t)row * a.ldc + c0;
 #pragma unroll
             for (int t = 0; t < T; ++t)
-                if (colok[t]) vstore<V, NTC>(dst + t * GV, acc[t]);
+                if (colok[t]) vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
         }
         return;
     }
@@ -225,7 +227,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         float *dst = a.C + (int64_t)(r0 + ri) * a.ldc + c0;
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            if (colok[t]) vstore<V, NTC>(dst + t * GV, acc[t]);
+            if (colok[t]) vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
     }
 }
 
@@ -264,7 +266,7 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
         float *dst = a.C + row * a.ldc + c0;
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            if (colok[t]) vstore<V, NTC>(dst + t * GV, acc[t]);
+            if (colok[t]) vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
     }
 }
 
@@ -307,6 +309,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const FixupArgs a) {
     for (int c = threadIdx.x; c < a.n; c += kBlock) {
         float sum = src[c];
         for (int i = 1; i < d.z; ++i) sum += src[(int64_t)i * a.partial_stride + c];
+        if (a.bias) sum += a.bias[c];
+        if (a.act == 1) sum = fmaxf(sum, 0.f);
         dst[c] = sum;
     }
 }
@@ -338,7 +342,9 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
     }
     const int lanes = (n + mp.V - 1) / mp.V;
     if (lanes <= kWave) {
-        int g = 4;
+        // n <= 4 (SpMV and its neighbours): one lane per group, the 64 lanes of a wavefront take 64 entries
+        // of a row (or 64 short rows of a window) per step and are combined by the xor butterfly
+        int g = 1;
         while (g < lanes) g <<= 1;
         mp.G = g;
         mp.T = 1;
@@ -375,17 +381,15 @@ static int64_t grid_size(const Mapping &mp, int64_t per_tile) {
 typedef void (*kernel_fn)(const ExecArgs);
 
 #define SCORCH_PICK_NT(KERNEL, V, G, T, U)                                  \
-    switch (NT & 3) {                                                       \
-        case 0: return KERNEL<V, G, T, U, 0>;                               \
-        case 1: return KERNEL<V, G, T, U, 1>;                               \
-        case 2: return KERNEL<V, G, T, U, 2>;                               \
-        default: return KERNEL<V, G, T, U, 3>;                              \
-    }
+    if (NT & 1) return KERNEL<V, G, T, U, 1>;                               \
+    return KERNEL<V, G, T, U, 0>;
 #define SCORCH_PICK_U(KERNEL, V, G, T)                                      \
     if (U >= 8) { SCORCH_PICK_NT(KERNEL, V, G, T, 8) } else { SCORCH_PICK_NT(KERNEL, V, G, T, 4) }
 #define SCORCH_PICK_G(KERNEL, V)                                            \
     if (T == 2) { SCORCH_PICK_U(KERNEL, V, 64, 2) }                         \
     switch (G) {                                                            \
+        case 1: SCORCH_PICK_U(KERNEL, V, 1, 1)                              \
+        case 2: SCORCH_PICK_U(KERNEL, V, 2, 1)                              \
         case 4: SCORCH_PICK_U(KERNEL, V, 4, 1)                              \
         case 8: SCORCH_PICK_U(KERNEL, V, 8, 1)                              \
         case 16: SCORCH_PICK_U(KERNEL, V, 16, 1)                            \
@@ -400,15 +404,19 @@ typedef void (*kernel_fn)(const ExecArgs);
     }
 
 static kernel_fn pick_fused(int V, int G, int T, int U, int NT) { SCORCH_PICK(spmm_fused_kernel) }
-static kernel_fn pick_natural(int V, int G, int T, int U, int NT) { SCORCH_PICK(spmm_natural_kernel) }
+static kernel_fn pick_natural(int V, int G, int T, int U, int NT) {
+    U = 8;  // the plan-free path is compiled for one unroll depth and streaming stores only
+    NT = 1;
+    SCORCH_PICK(spmm_natural_kernel)
+}
 
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
 
 scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
-                               hipStream_t stream) {
+                               const float *bias, int32_t act, hipStream_t stream) {
     if (plan->params.PANEL && panel_operands_ok(plan->n, B, ldb, C, ldc))
-        return launch_panel(plan, rowptr, colidx, vals, B, ldb, C, ldc, stream);
+        return launch_panel(plan, rowptr, colidx, vals, B, ldb, C, ldc, bias, act, stream);
     const Mapping mp = pick_mapping(plan->n, B, ldb, C, ldc, plan->params.SLICED != 0);
     ExecArgs a{};
     a.rowptr = rowptr;
@@ -435,6 +443,8 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     a.LW = plan->params.LW;
     a.ncoltiles = mp.ncoltiles;
     a.xcd_slices = mp.xcd_slices;
+    a.bias = bias;
+    a.act = act;
     const int64_t per_tile = (int64_t)a.nb_items + a.nb_wave + a.nb_win;
     const int64_t grid = grid_size(mp, per_tile);
     if (grid > 0x7fffffffLL) {
@@ -464,6 +474,8 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
         f.n = plan->n;
         f.n_split = plan->n_split;
         f.partial_stride = plan->layout.partial_stride;
+        f.bias = bias;
+        f.act = act;
         hipLaunchKernelGGL(spmm_fixup_kernel, dim3((uint32_t)plan->n_split), dim3(kBlock), 0, stream, f);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "launch spmm_fixup_kernel");

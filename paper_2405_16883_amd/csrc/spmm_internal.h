@@ -31,7 +31,7 @@ struct PlanParams {
     int32_t CH;     // wave rows:  LW < len <= CH
     int32_t BCH;    // block rows: pieces of at most BCH entries
     int32_t U;      // gathers in flight per lane group (4 or 8)
-    int32_t NT;     // bit 0: streaming stores for C; bit 1: streaming loads for colidx/vals
+    int32_t NT;     // bit 0: streaming (non-temporal) stores for C
     int32_t SLICED; // 1: the workload suits XCD-sliced execution (see want_sliced)
     int32_t PACK;   // 1: sliced execution gathers from a slice-major copy of B made at every call
     int32_t PANEL;  // 1: dense-ish sorted rows: stream B through LDS in k-panels (spmm_panel.hip)
@@ -71,6 +71,8 @@ struct ExecArgs {
     int32_t ncoltiles;
     int32_t xcd_slices;  // 0 = tile-major grid, else XCD-sliced (see tile_of_workgroup)
     int64_t b_tile_stride;  // 0: B is the caller's row-major matrix; else B is slice-major, floats per slice
+    const float *bias;      // epilogue: n floats added to every row of C, or nullptr
+    int32_t act;            // epilogue: 0 identity, 1 ReLU
 };
 
 struct PanelArgs {
@@ -84,6 +86,8 @@ struct PanelArgs {
     int32_t nrb;     // row blocks of 4*RW rows
     int32_t ntiles;  // 256-column tiles
     int32_t xcd_slices;
+    const float *bias;
+    int32_t act;
 };
 
 struct FixupArgs {
@@ -92,6 +96,8 @@ struct FixupArgs {
     float *C;
     int64_t ldc;
     int32_t n, n_split, partial_stride;
+    const float *bias;
+    int32_t act;
 };
 
 #if defined(__HIPCC__)
@@ -151,7 +157,7 @@ scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, cons
 // spmm_exec.hip
 scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
-                               hipStream_t stream);
+                               const float *bias, int32_t act, hipStream_t stream);
 scorch_status_t launch_pack_b(const float *B, int64_t ldb, int32_t k, int32_t n, int32_t W, float *Bp,
                               hipStream_t stream);
 int64_t xcd_grid_size(int32_t xcd_slices, int32_t ncoltiles, int64_t per_tile);
@@ -161,7 +167,7 @@ int32_t xcd_slots_for(int32_t ncoltiles);
 bool panel_operands_ok(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc);
 scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                              const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
-                             hipStream_t stream);
+                             const float *bias, int32_t act, hipStream_t stream);
 
 // sddmm_exec.hip (plan == nullptr: plan-free, one wavefront per row)
 scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t d, const int32_t *rowptr,

@@ -106,7 +106,16 @@ __global__ __launch_bounds__(kBlock) void spmm_panel_kernel(const PanelArgs a) {
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         const int64_t row = row_base + r;
-        if (row < a.m && colok) __builtin_nontemporal_store(acc[r], reinterpret_cast<f4 *>(a.C + row * a.ldc + c0));
+        if (row < a.m && colok) {
+            f4 v = acc[r];
+            if (a.bias)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] += a.bias[c0 + i];
+            if (a.act == 1)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = fmaxf(v[i], 0.f);
+            __builtin_nontemporal_store(v, reinterpret_cast<f4 *>(a.C + row * a.ldc + c0));
+        }
     }
 }
 
@@ -117,7 +126,7 @@ bool panel_operands_ok(int32_t n, const float *B, int64_t ldb, const float *C, i
 
 scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                              const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
-                             hipStream_t stream) {
+                             const float *bias, int32_t act, hipStream_t stream) {
     constexpr int RW = 16;
     float *Bp = reinterpret_cast<float *>(plan->workspace + plan->layout.off_bpack);
     scorch_status_t st = launch_pack_b(B, ldb, plan->k, plan->n, kPanelCols, Bp, stream);
@@ -135,6 +144,8 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
     a.nrb = (plan->m + kWavesPerBlock * RW - 1) / (kWavesPerBlock * RW);
     a.ntiles = (plan->n + kPanelCols - 1) / kPanelCols;
     a.xcd_slices = xcd_slots_for(a.ntiles);
+    a.bias = bias;
+    a.act = act;
     const int64_t grid = xcd_grid_size(a.xcd_slices, a.ntiles, a.nrb);
     if (grid > 0x7fffffffLL) {
         set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);

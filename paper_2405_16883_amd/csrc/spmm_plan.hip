@@ -277,7 +277,7 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     p.CH = std::max(p.CH, p.LW);
     p.BCH = std::max(p.BCH, 64);
     p.U = p.U >= 8 ? 8 : 4;
-    p.NT &= 3;
+    p.NT &= 1;
     return p;
 }
 

@@ -9,7 +9,7 @@ import os
 import numpy as np
 import pytest
 
-from oracle import spmm_csr_oracle
+from oracle import spmm_bias_act_oracle, spmm_csr_oracle
 from workloads import (csr_from_row_lengths, integer_valued, make_scaled_config, tiny_powerlaw,
                        uniform_rows, with_padding)
 
@@ -215,3 +215,24 @@ def test_stored_order_accumulation_is_sequential_fp64():
     big = np.float64(np.float32(1e16))
     C, _ = spmm_csr_oracle(1, 1, np.array([0, 3], np.int32), np.array([0, 1, 2], np.int32), vals, B)
     assert C[0, 0] == (big + 1.0) - big
+
+
+def test_bias_activation_layer_oracle():
+    # hand-worked on the 3x3 fixture: A.B = [[11 14],[0 0],[9 12]]; bias [-10, 1] -> [[1 15],[-10 1],[-1 13]];
+    # ReLU -> [[1 15],[0 1],[0 13]]
+    g = read_fixture("handworked_3x3.txt")
+    bias = np.array([-10.0, 1.0], dtype=np.float32)
+    C, T = spmm_bias_act_oracle(g["m"], g["n"], g["rowptr"], g["colidx"], g["vals"], g["B"], bias, relu=False)
+    assert np.array_equal(C, np.array([[1, 15], [-10, 1], [-1, 13]], dtype=np.float64))
+    assert np.array_equal(T, g["T"] + np.array([10.0, 1.0]))
+    C, _ = spmm_bias_act_oracle(g["m"], g["n"], g["rowptr"], g["colidx"], g["vals"], g["B"], bias, relu=True)
+    assert np.array_equal(C, np.array([[1, 15], [0, 1], [0, 13]], dtype=np.float64))
+    # no bias, no activation: the plain product; dense cross-check with numpy on a random pattern
+    p = csr_from_row_lengths([4, 0, 9, 2, 6], 12, 7, seed=21)
+    b = np.random.default_rng(1).standard_normal(7).astype(np.float32)
+    C0, T0 = oracle(p)
+    C1, T1 = spmm_bias_act_oracle(p.m, p.n, p.rowptr, p.colidx, p.vals, p.B, None, relu=False)
+    assert np.array_equal(C0, C1) and np.array_equal(T0, T1)
+    C2, _ = spmm_bias_act_oracle(p.m, p.n, p.rowptr, p.colidx, p.vals, p.B, b, relu=True)
+    ref = np.maximum(densify(p) @ p.B[:, :p.n].astype(np.float64) + b.astype(np.float64), 0.0)
+    assert np.all(np.abs(C2 - ref) <= 1e-12 * (T0 + 1)) and np.all(C2 >= 0) and np.array_equal(C2[1], np.maximum(b.astype(np.float64), 0))
