@@ -226,16 +226,6 @@ static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
     return slice_bytes <= kL2SliceBudget && b_bytes > kL2SliceBudget && nnz / m >= 32;
 }
 
-// The panel kernel streams all of B through LDS once per block of 64 rows of A, so it pays when a B row
-// staged in LDS is used by several of those rows: a few percent of the entries stored, long rows, enough
-// row blocks and column tiles to fill the chip.
-static bool want_panel(int32_t m, int32_t k, int64_t nnz, int32_t n) {
-    if (m < 512 || k < kPanelRows || n % 4 != 0 || n < 128) return false;
-    const double density = (double)nnz / ((double)m * (double)k);
-    const int64_t tasks = (int64_t)((m + 63) / 64) * ((n + kPanelCols - 1) / kPanelCols);
-    return density >= 0.03 && nnz / m >= 128 && tasks >= 256;
-}
-
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t) {
     PlanParams p;
     p.ALPHA = 4;
@@ -254,7 +244,6 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     // opt-in only.
     p.PANEL = 0;
     if (t.panel > 0) p.PANEL = (n % 4 == 0 && k > 0) ? 1 : 0;
-    (void)want_panel;
     // Enough independent wavefront tasks to fill 256 CUs several times over, but pieces long
     // enough that the per-piece overhead stays small.
     const int64_t coltiles = p.SLICED ? (n + kSliceCols - 1) / kSliceCols : std::max<int64_t>(1, (n + 511) / 512);
