@@ -126,6 +126,25 @@ def time_sddmm(res, torch, sp, d, steps=30, warmup=5):
             "frac_hbm": bytes_min / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def time_graph_replay(res, torch, sp, steps_per_graph=20, replays=10):
+    """Per-step time when `steps_per_graph` planned calls are recorded into one HIP graph (launch overhead amortised)."""
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            for _ in range(steps_per_graph):
+                sp.scorch_spmm_csr_planned(res.plan, res.rowptr, res.colidx, res.vals, res.B, res.C, stream=side)
+    torch.cuda.synchronize()
+    graph.replay()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(replays):
+        graph.replay()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) * 1e3 / (replays * steps_per_graph)
+
+
 def cpu_baseline_and_check(res, torch, target_nnz=12_000_000):
     """Time the serial fp64 oracle on a contiguous block of rows (~target_nnz entries) and compare the GPU rows."""
     from oracle import spmm_csr_oracle  # the only place the benchmark touches the oracle
@@ -244,13 +263,17 @@ def main():
                 continue
             torch.cuda.empty_cache()
             r, o = run_config(cfg, 50 if cfg != 4 else 20, 5, cold_steps=10 if cfg != 4 else 3)
+            if cfg == 1:
+                o["graph_replay_ms_per_step"] = time_graph_replay(r, torch, sp)
+                log(f"[bench] cfg 1 recorded into a HIP graph (20 steps per replay): {o['graph_replay_ms_per_step'] * 1e3:.2f} us per step")
             if cfg == 3:
                 o["sddmm"] = time_sddmm(r, torch, sp, 128)
                 log(f"[bench] sddmm on cfg 3 pattern, d=128: {o['sddmm']['event_ms_mean']:.4f} ms  {o['sddmm']['gflops']:.0f} GFLOP/s  "
                     f"{100 * o['sddmm']['frac_hbm']:.1f}% of HBM peak (min-traffic model)")
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
                                                            "gbs_min_traffic", "frac_hbm", "cold_event_ms_mean",
-                                                           "cold_frac_hbm", "plan_ms") + (("sddmm",) if "sddmm" in o else ())}
+                                                           "cold_frac_hbm", "plan_ms") + (("sddmm",) if "sddmm" in o else ())
+                                        + (("graph_replay_ms_per_step",) if "graph_replay_ms_per_step" in o else ())}
             del r
 
     line = {
