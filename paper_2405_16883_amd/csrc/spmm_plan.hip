@@ -226,6 +226,19 @@ static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
     return slice_bytes <= kL2SliceBudget && b_bytes > kL2SliceBudget && nnz / m >= 32;
 }
 
+// The panel kernel (spmm_panel.hip) streams all of B through LDS once per block of rows of A, a cost that does
+// not depend on nnz, and then pays per entry about 40 % less than the gather kernels.  Measured on 4096 x 16384
+// weights with n = 2048 it wins from about 4 % stored entries upwards (5 %: 0.99 against 1.26 ms, 10 %: 1.45 against
+// 2.29 ms, 50 %: 4.2 against 11.7 ms) and loses below (2.5 %: 0.77 against 0.70 ms); with fewer than two workgroups
+// per CU (64 rows x 256 columns each) it loses at any density.  Returns the kernel shape (0 = do not use).
+static int32_t want_panel(int32_t m, int32_t k, int64_t nnz, int32_t n) {
+    if (m <= 0 || k < 1024 || n % 4 != 0 || n < kPanelCols) return 0;
+    const double density = (double)nnz / ((double)m * (double)k);
+    const int64_t tasks = (int64_t)((m + 63) / 64) * ((n + kPanelCols - 1) / kPanelCols);
+    if (density < 0.04 || nnz / m < 128 || tasks < 512) return 0;
+    return (density >= 0.08 && n >= 2 * kPanelCols) ? 2 : 1;  // 2: 512-column tiles, 32 rows per workgroup
+}
+
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t) {
     PlanParams p;
     p.ALPHA = 4;
@@ -239,11 +252,8 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     // dense slice-major copy instead (costs one read and one write of B per call).
     p.PACK = (p.SLICED && n > 128) ? 1 : 0;
     if (t.pack >= 0) p.PACK = (p.SLICED && t.pack != 0) ? 1 : 0;
-    // The panel kernel is correct but, as measured on the pruned-weight workload, still slower than the
-    // XCD-sliced gather (3.2 ms against 2.2 ms: issue-bound on v_readlane and scalar bookkeeping), so it is
-    // opt-in only.
-    p.PANEL = 0;
-    if (t.panel > 0) p.PANEL = (n % 4 == 0 && k > 0) ? 1 : 0;
+    p.PANEL = want_panel(m, k, nnz, n);
+    if (t.panel >= 0) p.PANEL = (t.panel > 0 && n % 4 == 0 && k > 0) ? t.panel : 0;
     // Enough independent wavefront tasks to fill 256 CUs several times over, but pieces long
     // enough that the per-piece overhead stays small.
     const int64_t coltiles = p.SLICED ? (n + kSliceCols - 1) / kSliceCols : std::max<int64_t>(1, (n + 511) / 512);
@@ -298,7 +308,7 @@ WorkspaceLayout layout_workspace(int32_t m, int32_t k, int64_t nnz, int32_t n, c
     L.off_partials = off;
     off = align_up(off + (uint64_t)L.cap_slots * L.partial_stride * 4, 256);
     L.off_bpack = off;
-    if (p.PACK || p.PANEL) off = align_up(off + (uint64_t)k * ((n + kPanelCols - 1) / kPanelCols) * kPanelCols * 4, 256);
+    if (p.PACK || p.PANEL) off = align_up(off + (uint64_t)k * ((n + 2 * kPanelCols - 1) / (2 * kPanelCols)) * (2 * kPanelCols) * 4, 256);
     L.total = std::max<uint64_t>(off, 256);
     return L;
 }

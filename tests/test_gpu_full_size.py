@@ -14,7 +14,7 @@ import torch
 import paper_2405_16883_amd as sp
 from workloads import integer_valued, make_config
 
-from gpu_util import ATOL, RTOL_T, DeviceProblem, check_against_oracle
+from gpu_util import ATOL, RTOL_T, DeviceProblem, check_against_oracle, tuning
 
 pytestmark = pytest.mark.gpu
 CACHE = os.environ.get("SCORCH_WORKLOAD_CACHE")
@@ -76,7 +76,14 @@ def test_full_size_sampled_rows_and_row_sums(cfg):
     Cn = d.run_natural()
     check_against_oracle(p, Cn, d.ldc, rows=rows, label=f"workload {cfg} plan-free, sampled rows")
     del Cn, C
+    assert plan.info().mode == (2 if cfg == 5 else 0)  # workload 5 runs the panel kernel by default
     plan.destroy()
+    if cfg == 5:
+        with tuning("panel=0"):  # the XCD-sliced gather kernel (with the packed copy of B) on the same workload
+            plan = d.make_plan()
+            assert plan.info().mode == 1
+            check_against_oracle(p, d.run_planned(plan), d.ldc, rows=rows, label="workload 5 sliced gather, sampled rows")
+            plan.destroy()
     # integer twin: bit-exact on the sampled rows
     q = integer_valued(p, seed=4)
     d.Bfull.copy_(torch.from_numpy(q.B))

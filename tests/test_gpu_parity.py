@@ -105,16 +105,17 @@ def test_xcd_sliced_column_mapping(n):
             run_both(with_padding(p, n + 4), ldc=n + 8, label=f"sliced n={n} padded [{tune}]")
 
 
+@pytest.mark.parametrize("shape", [1, 2])
 @pytest.mark.parametrize("m,k,n", [(64, 64, 256), (130, 200, 128), (515, 1000, 512), (300, 77, 260), (257, 4100, 1028),
                                    (1000, 333, 2048)])
-def test_panel_kernel_forced(m, k, n):
+def test_panel_kernel_forced(m, k, n, shape):
     """The LDS panel kernel on shapes with ragged row blocks, ragged last panel and ragged last column tile."""
     rng = np.random.default_rng(m + n)
     lens = rng.integers(0, max(2, k // 3), size=m)
     lens[rng.integers(0, m, size=5)] = 0
     lens[0] = min(k, 700)  # a row whose 64-entry register window slides many times
     p = csr_from_row_lengths(lens, k, n, seed=m, duplicates=False)
-    with tuning("panel=1"):
+    with tuning(f"panel={shape}"):
         d = DeviceProblem(p)
         plan = d.make_plan()
         assert plan.info().mode == 2
