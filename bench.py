@@ -187,7 +187,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build is single-GPU (one MI355X); --gpus must be 1. "
-              "Sharding across GPUs is described in DESIGN.md and not built.", file=sys.stderr)
+              "No multi-GPU path is built.", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -40,6 +40,16 @@ static scorch_status_t check_operands(int32_t m, int32_t k, int32_t n, const voi
     return SCORCH_OK;
 }
 
+// A plan's row lists and partial rows live in memory of the device that was current when it was made.
+static scorch_status_t check_plan_device(const scorch_spmm_plan_t *plan) {
+    int dev = -1;
+    if (hipGetDevice(&dev) == hipSuccess && plan->device >= 0 && dev != plan->device) {
+        set_error("plan was made on device %d but device %d is current", plan->device, dev);
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    return SCORCH_OK;
+}
+
 }  // namespace scorch
 
 using namespace scorch;
@@ -139,6 +149,7 @@ scorch_status_t scorch_spmm_csr_planned(const scorch_spmm_plan_t *plan, const in
         set_error("colidx, vals and B must not be NULL when nnz > 0");
         return SCORCH_ERR_INVALID_ARG;
     }
+    if ((st = check_plan_device(plan)) != SCORCH_OK) return st;
     return launch_planned(plan, rowptr, colidx, vals, B, ldb, C, ldc, nullptr, 0, static_cast<hipStream_t>(stream));
 }
 
@@ -160,6 +171,7 @@ scorch_status_t scorch_spmm_csr_planned_epilogue(const scorch_spmm_plan_t *plan,
         set_error("colidx, vals and B must not be NULL when nnz > 0");
         return SCORCH_ERR_INVALID_ARG;
     }
+    if ((st = check_plan_device(plan)) != SCORCH_OK) return st;
     return launch_planned(plan, rowptr, colidx, vals, B, ldb, C, ldc, bias, activation,
                           static_cast<hipStream_t>(stream));
 }
@@ -209,6 +221,7 @@ scorch_status_t scorch_sddmm_csr_planned(const scorch_spmm_plan_t *plan, int32_t
         set_error("sddmm: colidx, vals and out_vals must not be NULL when nnz > 0");
         return SCORCH_ERR_INVALID_ARG;
     }
+    if ((st = check_plan_device(plan)) != SCORCH_OK) return st;
     return launch_sddmm(plan, plan->m, d, rowptr, colidx, vals, B, ldb, Ct, ldct, out_vals,
                         static_cast<hipStream_t>(stream));
 }
