@@ -180,6 +180,18 @@ scorch_status_t scorch_sddmm_csr_planned(const scorch_spmm_plan_t *plan, int32_t
                                          const float *B, int32_t ldb, const float *Ct, int32_t ldct,
                                          float *out_vals, void *stream);
 
+/*
+ * Row pointers for a row-major coordinate list (paper, Appendix C: sparse tensors default to the coordinate
+ * format; a COO matrix lists (row, column, value) triples).  Given the row coordinates of nnz entries sorted by
+ * row (non-decreasing), writes rowptr_out[0..m] such that the entries of row i are [rowptr_out[i], rowptr_out[i+1]);
+ * the column and value arrays of the list then serve unchanged as colidx and vals of the CSR calls above.
+ * row_idx: int32[nnz], device, each in [0, m).  rowptr_out: int32[m+1], device.  bad_flag: int32[1], device, or
+ * NULL; it is set to 1 when the list is not sorted by row or holds a row outside [0, m) (rowptr_out is then
+ * unspecified) and left untouched otherwise -- clear it before the call.  Enqueues one kernel, never waits.
+ */
+scorch_status_t scorch_coo_to_csr_rowptr(int32_t m, int64_t nnz, const int32_t *row_idx, int32_t *rowptr_out,
+                                         int32_t *bad_flag, void *stream);
+
 /* Static text for a status code. */
 const char *scorch_status_string(scorch_status_t status);
 

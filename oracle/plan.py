@@ -62,3 +62,12 @@ def plan_oracle(rowptr: np.ndarray, BN: int, ALPHA: int, LW: int, CH: int, BCH: 
         "n_slots": np.int64(slot),
         "n_short": np.int64(int((cls == 0).sum())),
     }
+
+
+def coo_rowptr_oracle(m: int, row_idx: np.ndarray) -> np.ndarray:
+    """Row pointers of a coordinate list (paper, Appendix C, coordinate format) whose entries are sorted by row:
+    rowptr[i] = number of entries with row < i, i.e. the running sum of the per-row counts."""
+    counts = np.bincount(np.asarray(row_idx, dtype=np.int64), minlength=m)
+    out = np.zeros(m + 1, dtype=np.int64)
+    np.cumsum(counts, out=out[1:])
+    return out.astype(np.int32)

@@ -24,7 +24,7 @@ SCORCH_ERR_HIP = -4
 EXPORTS = (
     "scorch_spmm_csr", "scorch_spmm_plan_workspace_bytes", "scorch_spmm_plan", "scorch_spmm_csr_planned",
     "scorch_spmm_plan_destroy", "scorch_spmm_plan_info", "scorch_status_string", "scorch_last_error",
-    "scorch_sddmm_csr", "scorch_sddmm_csr_planned", "scorch_spmm_csr_planned_epilogue",
+    "scorch_sddmm_csr", "scorch_sddmm_csr_planned", "scorch_spmm_csr_planned_epilogue", "scorch_coo_to_csr_rowptr",
 )
 
 
@@ -75,6 +75,8 @@ def load_library() -> ctypes.CDLL:
     lib.scorch_spmm_plan_info.argtypes = [vp, ctypes.POINTER(PlanInfo)]
     lib.scorch_spmm_csr_planned_epilogue.restype = i32
     lib.scorch_spmm_csr_planned_epilogue.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp, i32, vp]
+    lib.scorch_coo_to_csr_rowptr.restype = i32
+    lib.scorch_coo_to_csr_rowptr.argtypes = [i32, i64, vp, vp, vp, vp]
     lib.scorch_sddmm_csr.restype = i32
     lib.scorch_sddmm_csr.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp, vp]
     lib.scorch_sddmm_csr_planned.restype = i32
@@ -221,3 +223,14 @@ def scorch_spmm_csr_planned_epilogue(plan: SpmmPlan, rowptr: torch.Tensor, colid
                                                 _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(B, torch.float32, "B"),
                                                 _ld(B, "B"), _dev_ptr(bias, torch.float32, "bias"), activation,
                                                 _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))
+
+
+def scorch_coo_to_csr_rowptr(m: int, row_idx: torch.Tensor, rowptr_out: torch.Tensor,
+                             bad_flag: Optional[torch.Tensor] = None, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """rowptr_out[0..m] for a coordinate list whose int32 row coordinates ``row_idx`` are sorted by row."""
+    lib = load_library()
+    if rowptr_out.numel() != m + 1:
+        raise ValueError("rowptr_out must have m + 1 entries")
+    _check(lib.scorch_coo_to_csr_rowptr(m, row_idx.numel(), _dev_ptr(row_idx, torch.int32, "row_idx"),
+                                        _dev_ptr(rowptr_out, torch.int32, "rowptr_out"),
+                                        _dev_ptr(bad_flag, torch.int32, "bad_flag"), _stream_handle(stream)))

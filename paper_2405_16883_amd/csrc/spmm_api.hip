@@ -226,6 +226,19 @@ scorch_status_t scorch_sddmm_csr_planned(const scorch_spmm_plan_t *plan, int32_t
                         static_cast<hipStream_t>(stream));
 }
 
+scorch_status_t scorch_coo_to_csr_rowptr(int32_t m, int64_t nnz, const int32_t *row_idx, int32_t *rowptr_out,
+                                         int32_t *bad_flag, void *stream) {
+    if (m < 0 || nnz < 0 || !rowptr_out || (nnz > 0 && !row_idx)) {
+        set_error("coo_to_csr_rowptr: bad argument");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    if (nnz >= (int64_t)1 << 31) {
+        set_error("nnz = %lld does not fit int32 row pointers", (long long)nnz);
+        return SCORCH_ERR_UNSUPPORTED;
+    }
+    return launch_coo_rowptr(m, nnz, row_idx, rowptr_out, bad_flag, static_cast<hipStream_t>(stream));
+}
+
 scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan) {
     delete plan;
     return SCORCH_OK;

@@ -154,6 +154,9 @@ scorch_status_t hip_fail(hipError_t e, const char *what);
 scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                            hipStream_t stream);
 
+scorch_status_t launch_coo_rowptr(int32_t m, int64_t nnz, const int32_t *row_idx, int32_t *rowptr, int32_t *bad_flag,
+                                  hipStream_t stream);
+
 // spmm_exec.hip
 scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,

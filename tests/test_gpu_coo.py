@@ -1,0 +1,54 @@
+"""Coordinate-list input: row pointers built on the device match the oracle bit for bit, and SpMM through them
+matches the SpMM oracle."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_16883_amd as sp
+from oracle import coo_rowptr_oracle
+from workloads import csr_from_row_lengths, make_scaled_config
+
+from gpu_util import DeviceProblem, check_against_oracle
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def device_rowptr(m, rows):
+    r = torch.from_numpy(np.ascontiguousarray(rows, dtype=np.int32)).to(DEV)
+    out = torch.full((m + 1,), -5, dtype=torch.int32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    sp.scorch_coo_to_csr_rowptr(m, r, out, flag)
+    torch.cuda.synchronize()
+    return out.cpu().numpy(), int(flag.item())
+
+
+@pytest.mark.parametrize("lens", [[0] * 50, [7], [0, 0, 5, 0, 0, 0, 9, 0], [3] * 1000, [0] * 999 + [1], [100000, 0, 1]])
+def test_rowptr_edge_patterns(lens):
+    p = csr_from_row_lengths(lens, 1000, 4, seed=1, duplicates=True)
+    rows = np.repeat(np.arange(p.m), p.row_lengths)
+    got, bad = device_rowptr(p.m, rows)
+    assert bad == 0 and np.array_equal(got, coo_rowptr_oracle(p.m, rows)) and np.array_equal(got, p.rowptr)
+
+
+def test_unsorted_or_out_of_range_rows_raise_the_flag():
+    assert device_rowptr(4, [0, 2, 1, 3])[1] == 1
+    assert device_rowptr(4, [0, 1, 4])[1] == 1
+    assert device_rowptr(4, [-1, 1])[1] == 1
+    assert device_rowptr(4, [0, 1, 1, 3])[1] == 0
+
+
+@pytest.mark.parametrize("cfg,scale", [(1, 1.0), (3, 0.08), (5, 0.06)])
+def test_spmm_from_a_coordinate_list(cfg, scale):
+    p = make_scaled_config(cfg, scale, seed=5)
+    rows = np.repeat(np.arange(p.m), p.row_lengths)
+    d = DeviceProblem(p)
+    r = torch.from_numpy(rows.astype(np.int32)).to(DEV)
+    rowptr = torch.empty(p.m + 1, dtype=torch.int32, device=DEV)
+    sp.scorch_coo_to_csr_rowptr(p.m, r, rowptr)
+    plan = sp.scorch_spmm_plan(p.m, p.k, p.n, rowptr, p.nnz, colidx=d.colidx)
+    d.reset_C()
+    sp.scorch_spmm_csr_planned(plan, rowptr, d.colidx, d.vals, d._B_arg(), d._C_arg())
+    torch.cuda.synchronize()
+    check_against_oracle(p, d.Cfull.cpu().numpy(), d.ldc, label=f"{p.name} from COO")
+    plan.destroy()

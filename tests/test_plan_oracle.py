@@ -62,3 +62,13 @@ def test_plan_edge_cases():
     assert P["row_class"].tolist() == [1, 2, 2, 2, 0, 1, 0]
     assert P["items"][:, 3].tolist() == [-1, -1, 0, 1]
     assert P["split"].tolist() == [[3, 0, 2, 0]]
+
+
+def test_coo_rowptr_oracle_against_the_generators_own_row_pointers():
+    from oracle import coo_rowptr_oracle
+    for cfg, scale in ((1, 0.3), (3, 0.02), (5, 0.03)):
+        p = make_scaled_config(cfg, scale, seed=2)
+        rows = np.repeat(np.arange(p.m), p.row_lengths).astype(np.int32)  # the coordinate list of the same matrix
+        assert np.array_equal(coo_rowptr_oracle(p.m, rows), p.rowptr)
+    assert coo_rowptr_oracle(4, np.zeros(0, np.int32)).tolist() == [0, 0, 0, 0, 0]
+    assert coo_rowptr_oracle(5, np.array([1, 1, 3], np.int32)).tolist() == [0, 0, 2, 2, 3, 3]
