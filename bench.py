@@ -219,6 +219,23 @@ def main():
             _, evc = time_steps(res, torch, cold_steps, 1, flush=flush)
             out["cold_event_ms_mean"] = float(np.mean(evc))
             out["cold_frac_hbm"] = bytes_min / (float(np.mean(evc)) * 1e-3) / 1e9 / HBM_PEAK_GBS
+        # the plan-free entry point (scorch_spmm_csr) on the same operands, a few calls
+        def natural():
+            sp.scorch_spmm_csr(p.m, p.k, p.n, res.rowptr, res.colidx, res.vals, res.B, res.C)
+        for _ in range(2):
+            natural()
+        torch.cuda.synchronize()
+        nat = []
+        for _ in range(5):
+            a_, b_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a_.record()
+            natural()
+            b_.record()
+            nat.append((a_, b_))
+        torch.cuda.synchronize()
+        out["plan_free_event_ms_mean"] = float(np.mean([x.elapsed_time(y) for x, y in nat]))
+        res.step()  # leave the planned result in C
+        torch.cuda.synchronize()
         info = res.plan.info()
         out.update({"workload": CONFIG_NAMES[cfg], "m": p.m, "k": p.k, "n": p.n, "nnz": p.nnz,
                     "bytes_min": bytes_min, "plan_ms": res.plan_ms,
@@ -272,7 +289,7 @@ def main():
                     f"{100 * o['sddmm']['frac_hbm']:.1f}% of HBM peak (min-traffic model)")
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
                                                            "gbs_min_traffic", "frac_hbm", "cold_event_ms_mean",
-                                                           "cold_frac_hbm", "plan_ms") + (("sddmm",) if "sddmm" in o else ())
+                                                           "cold_frac_hbm", "plan_ms", "plan_free_event_ms_mean") + (("sddmm",) if "sddmm" in o else ())
                                         + (("graph_replay_ms_per_step",) if "graph_replay_ms_per_step" in o else ())}
             del r
 
@@ -291,6 +308,7 @@ def main():
         "data": "synthetic",
         "config": {"workload": name, "m": head["m"], "k": head["k"], "n": head["n"], "nnz": head["nnz"],
                    "seed": args.seed, "plan": head["plan"], "plan_ms": head["plan_ms"]},
+        "plan_free_ms_per_step": head["plan_free_event_ms_mean"],
         "hbm_gbs_min_traffic": head["gbs_min_traffic"],
         "hbm_frac_of_peak": head["frac_hbm"],
         "cold_cache": {"event_ms_mean": head.get("cold_event_ms_mean"), "frac_hbm": head.get("cold_frac_hbm")},

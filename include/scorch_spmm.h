@@ -54,9 +54,10 @@ enum {
 typedef struct scorch_spmm_plan_s scorch_spmm_plan_t; /* small host-side handle */
 
 /*
- * Plan-free SpMM: C = A.B with one wavefront per row of A in natural row order.  Always
- * available and correct for any valid input; no load balancing, so rows with very many
- * entries run on a single wavefront.  (Definition: see the top of this file.)
+ * Plan-free SpMM: C = A.B in natural row order, one wavefront per row and the four wavefronts
+ * of a workgroup together on rows with more than 2048 entries.  Always available and correct for
+ * any valid input; no load balancing beyond that, so a row with very many entries still runs
+ * on a single workgroup.  (Definition: see the top of this file.)
  */
 scorch_status_t scorch_spmm_csr(int32_t m, int32_t k, int32_t n,
                                 const int32_t *rowptr, const int32_t *colidx, const float *vals,

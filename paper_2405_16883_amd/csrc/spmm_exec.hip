@@ -231,16 +231,21 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     }
 }
 
-// Plan-free path: one wavefront per row in natural order (any row length).
+// Plan-free path: a workgroup takes 4 consecutive rows in natural order.  A row of up to kNaturalLong entries
+// is done by its own wavefront; a longer one by all 4 wavefronts together (interleaved 64-entry chunks, LDS tree),
+// which shortens the serial chain of a heavy row fourfold without any scratch memory.
+constexpr int kNaturalLong = 2048;
+
 template <int V, int G, int T, int U, int NT>
 __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) {
     using vec = typename Vec<V>::type;
     constexpr int GV = G * V;
     constexpr int TW = GV * T;
     constexpr bool NTC = (NT & 1) != 0;
-    constexpr bool NTA = (NT & 2) != 0;
     __shared__ int s_col[kWavesPerBlock * kWave];
     __shared__ float s_val[kWavesPerBlock * kWave];
+    __shared__ float s_red[kWavesPerBlock * TW];
+    __shared__ int s_p0[kWavesPerBlock], s_p1[kWavesPerBlock];
     const int tid = threadIdx.x;
     const int wv = tid >> 6;
     const int lane = tid & 63;
@@ -249,8 +254,8 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     const uint32_t per_tile = (uint32_t)a.nb_wave;
     const uint32_t ct = blockIdx.x / per_tile;
     const uint32_t b = blockIdx.x - ct * per_tile;
-    const int64_t row = (int64_t)b * kWavesPerBlock + wv;
-    if (row >= a.m) return;
+    const int64_t row0 = (int64_t)b * kWavesPerBlock;
+    const int64_t row = row0 + wv;
     const int c0 = (int)ct * TW + lig * V;
     bool colok[T];
 #pragma unroll
@@ -258,15 +263,66 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     vec acc[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-    const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
-    row_accumulate<V, G, T, U, NTA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, p0, p1, kWave,
-                                    a.colidx, a.vals, a.B + c0, a.ldb, colok);
-    reduce_groups<V, G, T>(acc);
-    if (grp == 0) {
-        float *dst = a.C + row * a.ldc + c0;
+    int p0 = 0, p1 = 0;
+    if (row < a.m) {
+        p0 = a.rowptr[row];
+        p1 = a.rowptr[row + 1];
+    }
+    if (lane == 0) {
+        s_p0[wv] = p0;
+        s_p1[wv] = p1;
+    }
+    __syncthreads();
+    if (row < a.m && p1 - p0 <= kNaturalLong) {
+        row_accumulate<V, G, T, U, false>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, p0, p1, kWave,
+                                          a.colidx, a.vals, a.B + c0, a.ldb, colok);
+        reduce_groups<V, G, T>(acc);
+        if (grp == 0) {
+            float *dst = a.C + row * a.ldc + c0;
 #pragma unroll
-        for (int t = 0; t < T; ++t)
-            if (colok[t]) vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
+            for (int t = 0; t < T; ++t)
+                if (colok[t])
+                    vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
+        }
+    }
+    // long rows of this workgroup, one after the other, all wavefronts on each (the loop is workgroup-uniform)
+    for (int w = 0; w < kWavesPerBlock; ++w) {
+        const int q0 = s_p0[w], q1 = s_p1[w];
+        if (q1 - q0 <= kNaturalLong) continue;
+#pragma unroll
+        for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
+        row_accumulate<V, G, T, U, false>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, q0 + wv * kWave, q1,
+                                          kBlock, a.colidx, a.vals, a.B + c0, a.ldb, colok);
+        reduce_groups<V, G, T>(acc);
+        __syncthreads();  // s_red of the previous long row has been read
+        if (grp == 0) {
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if constexpr (V == 1) s_red[wv * TW + t * GV + lig] = acc[t];
+                else
+#pragma unroll
+                    for (int i = 0; i < V; ++i) s_red[wv * TW + t * GV + lig * V + i] = acc[t][i];
+            }
+        }
+        __syncthreads();
+        if (wv == 0 && grp == 0) {
+            float *dst = a.C + (row0 + w) * a.ldc + c0;
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                if (!colok[t]) continue;
+                vec r;
+#pragma unroll
+                for (int i = 0; i < V; ++i) {
+                    const int o = t * GV + lig * V + i;
+                    float sum = s_red[o];
+#pragma unroll
+                    for (int x = 1; x < kWavesPerBlock; ++x) sum += s_red[x * TW + o];
+                    if constexpr (V == 1) r = sum;
+                    else r[i] = sum;
+                }
+                vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(r, a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
+            }
+        }
     }
 }
 
