@@ -89,10 +89,13 @@ __global__ __launch_bounds__(kBlock) void plan_count_kernel(const PlanArgs a) {
     }
 }
 
-// One workgroup turns each of the kQ count arrays into exclusive offsets and stores the totals.
+// One workgroup of 1024 threads turns each of the kQ count arrays into exclusive offsets and stores the totals:
+// every thread sums a contiguous slice, the 1024 slice sums are scanned with wavefront shuffles (16 wavefronts),
+// then every thread rewrites its slice.
 __global__ __launch_bounds__(1024) void plan_scan_kernel(const PlanArgs a) {
-    __shared__ int s_part[1024];
+    __shared__ int s_wave[16];
     const int tid = threadIdx.x;
+    const int lane = tid & 63, wv = tid >> 6;
     const int64_t per = (a.nblk + 1023) / 1024;
     for (int k = 0; k < kQ; ++k) {
         int32_t *c = a.counts + (int64_t)k * a.nblk;
@@ -100,25 +103,29 @@ __global__ __launch_bounds__(1024) void plan_scan_kernel(const PlanArgs a) {
         const int64_t hi = std::min<int64_t>(lo + per, a.nblk);
         int sum = 0;
         for (int64_t j = lo; j < hi; ++j) sum += c[j];
-        s_part[tid] = sum;
-        __syncthreads();
-        if (tid == 0) {
-            int run = 0;
-            for (int j = 0; j < 1024; ++j) {
-                const int t = s_part[j];
-                s_part[j] = run;
-                run += t;
-            }
-            a.totals[k] = run;
+        int inc = sum;
+#pragma unroll
+        for (int off = 1; off < kWave; off <<= 1) {
+            const int o = __shfl_up(inc, off, kWave);
+            if (lane >= off) inc += o;
         }
+        __syncthreads();  // s_wave of the previous quantity has been read
+        if (lane == kWave - 1) s_wave[wv] = inc;
         __syncthreads();
-        int run = s_part[tid];
+        int base = 0, total = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            const int t = s_wave[w];
+            if (w < wv) base += t;
+            total += t;
+        }
+        if (tid == 0) a.totals[k] = total;
+        int run = base + inc - sum;
         for (int64_t j = lo; j < hi; ++j) {
             const int t = c[j];
             c[j] = run;
             run += t;
         }
-        __syncthreads();
     }
 }
 

@@ -253,3 +253,14 @@ def test_runs_on_a_side_stream():
     s.synchronize()
     check_against_oracle(p, d.Cfull.cpu().numpy(), d.ldc, label="side stream")
     plan.destroy()
+
+
+@pytest.mark.parametrize("k,density", [(784, 0.2), (3072, 0.1), (3072, 0.5), (12288, 0.05)])
+def test_sparse_activation_times_dense_weight_shape(k, density):
+    """The sparse linear layer of the paper's autoencoder (Section 5.2, Table 2): a batch of 64 sparse input rows
+    times a dense k x 256 weight.  Few, long rows: the planner cuts them into pieces or hands them to the panel kernel."""
+    rng = np.random.default_rng(k)
+    lens = rng.binomial(k, density, size=64)
+    p = csr_from_row_lengths(lens, k, 256, seed=k)
+    run_both(p, label=f"batch 64 x {k} @ {k} x 256, density {density}")
+    run_both(integer_valued(p, seed=1), exact=True, label=f"batch 64 x {k} int")
