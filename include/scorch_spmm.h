@@ -193,6 +193,18 @@ scorch_status_t scorch_sddmm_csr_planned(const scorch_spmm_plan_t *plan, int32_t
 scorch_status_t scorch_coo_to_csr_rowptr(int32_t m, int64_t nnz, const int32_t *row_idx, int32_t *rowptr_out,
                                          int32_t *bad_flag, void *stream);
 
+/*
+ * Row pointers for a doubly compressed (DCSR) matrix (paper, Appendix C: both dimensions stored compressed, i.e.
+ * only the rows that hold entries are listed).  row_ids: int32[n_stored_rows], device, strictly increasing, each
+ * in [0, m): the ids of the stored rows.  row_pos: int32[n_stored_rows + 1], device: entries of row row_ids[r] are
+ * [row_pos[r], row_pos[r+1]), row_pos[n_stored_rows] = nnz.  Writes the CSR row pointers rowptr_out[0..m] (rows that
+ * are not listed come out empty); colidx and vals of the DCSR matrix serve unchanged.  bad_flag as for
+ * scorch_coo_to_csr_rowptr.  Enqueues one kernel, never waits.
+ */
+scorch_status_t scorch_dcsr_to_csr_rowptr(int32_t m, int32_t n_stored_rows, const int32_t *row_ids,
+                                          const int32_t *row_pos, int32_t *rowptr_out, int32_t *bad_flag,
+                                          void *stream);
+
 /* Static text for a status code. */
 const char *scorch_status_string(scorch_status_t status);
 

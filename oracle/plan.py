@@ -71,3 +71,13 @@ def coo_rowptr_oracle(m: int, row_idx: np.ndarray) -> np.ndarray:
     out = np.zeros(m + 1, dtype=np.int64)
     np.cumsum(counts, out=out[1:])
     return out.astype(np.int32)
+
+
+def dcsr_rowptr_oracle(m: int, row_ids: np.ndarray, row_pos: np.ndarray) -> np.ndarray:
+    """CSR row pointers of a doubly compressed matrix (paper, Appendix C): row row_ids[r] holds the entries
+    [row_pos[r], row_pos[r+1]); every other row is empty.  Written as per-row lengths and their running sum."""
+    lens = np.zeros(m, dtype=np.int64)
+    lens[np.asarray(row_ids, dtype=np.int64)] = np.diff(np.asarray(row_pos, dtype=np.int64))
+    out = np.zeros(m + 1, dtype=np.int64)
+    np.cumsum(lens, out=out[1:])
+    return out.astype(np.int32)

@@ -25,6 +25,7 @@ EXPORTS = (
     "scorch_spmm_csr", "scorch_spmm_plan_workspace_bytes", "scorch_spmm_plan", "scorch_spmm_csr_planned",
     "scorch_spmm_plan_destroy", "scorch_spmm_plan_info", "scorch_status_string", "scorch_last_error",
     "scorch_sddmm_csr", "scorch_sddmm_csr_planned", "scorch_spmm_csr_planned_epilogue", "scorch_coo_to_csr_rowptr",
+    "scorch_dcsr_to_csr_rowptr",
 )
 
 
@@ -77,6 +78,8 @@ def load_library() -> ctypes.CDLL:
     lib.scorch_spmm_csr_planned_epilogue.argtypes = [vp, vp, vp, vp, vp, i32, vp, i32, vp, i32, vp]
     lib.scorch_coo_to_csr_rowptr.restype = i32
     lib.scorch_coo_to_csr_rowptr.argtypes = [i32, i64, vp, vp, vp, vp]
+    lib.scorch_dcsr_to_csr_rowptr.restype = i32
+    lib.scorch_dcsr_to_csr_rowptr.argtypes = [i32, i32, vp, vp, vp, vp, vp]
     lib.scorch_sddmm_csr.restype = i32
     lib.scorch_sddmm_csr.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp, vp]
     lib.scorch_sddmm_csr_planned.restype = i32
@@ -234,3 +237,15 @@ def scorch_coo_to_csr_rowptr(m: int, row_idx: torch.Tensor, rowptr_out: torch.Te
     _check(lib.scorch_coo_to_csr_rowptr(m, row_idx.numel(), _dev_ptr(row_idx, torch.int32, "row_idx"),
                                         _dev_ptr(rowptr_out, torch.int32, "rowptr_out"),
                                         _dev_ptr(bad_flag, torch.int32, "bad_flag"), _stream_handle(stream)))
+
+
+def scorch_dcsr_to_csr_rowptr(m: int, row_ids: torch.Tensor, row_pos: torch.Tensor, rowptr_out: torch.Tensor,
+                              bad_flag: Optional[torch.Tensor] = None,
+                              stream: Optional[torch.cuda.Stream] = None) -> None:
+    """CSR row pointers of a doubly compressed matrix given the ids of its stored rows and their entry ranges."""
+    lib = load_library()
+    if rowptr_out.numel() != m + 1 or row_pos.numel() != row_ids.numel() + 1:
+        raise ValueError("rowptr_out needs m + 1 entries and row_pos one more entry than row_ids")
+    _check(lib.scorch_dcsr_to_csr_rowptr(m, row_ids.numel(), _dev_ptr(row_ids, torch.int32, "row_ids"),
+                                         row_pos.data_ptr(), _dev_ptr(rowptr_out, torch.int32, "rowptr_out"),
+                                         _dev_ptr(bad_flag, torch.int32, "bad_flag"), _stream_handle(stream)))

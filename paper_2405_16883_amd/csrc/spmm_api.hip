@@ -236,7 +236,19 @@ scorch_status_t scorch_coo_to_csr_rowptr(int32_t m, int64_t nnz, const int32_t *
         set_error("nnz = %lld does not fit int32 row pointers", (long long)nnz);
         return SCORCH_ERR_UNSUPPORTED;
     }
-    return launch_coo_rowptr(m, nnz, row_idx, rowptr_out, bad_flag, static_cast<hipStream_t>(stream));
+    return launch_rowptr_from_keys(m, nnz, row_idx, nullptr, false, rowptr_out, bad_flag,
+                                   static_cast<hipStream_t>(stream));
+}
+
+scorch_status_t scorch_dcsr_to_csr_rowptr(int32_t m, int32_t n_stored_rows, const int32_t *row_ids,
+                                          const int32_t *row_pos, int32_t *rowptr_out, int32_t *bad_flag,
+                                          void *stream) {
+    if (m < 0 || n_stored_rows < 0 || n_stored_rows > m || !rowptr_out || !row_pos || (n_stored_rows > 0 && !row_ids)) {
+        set_error("dcsr_to_csr_rowptr: bad argument");
+        return SCORCH_ERR_INVALID_ARG;
+    }
+    return launch_rowptr_from_keys(m, n_stored_rows, row_ids, row_pos, true, rowptr_out, bad_flag,
+                                   static_cast<hipStream_t>(stream));
 }
 
 scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan) {

@@ -103,8 +103,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     constexpr int S = kWave / G;
     constexpr int GV = G * V;
     constexpr int TW = GV * T;
-    constexpr bool NTC = (NT & 1) != 0;
-    constexpr bool NTA = (NT & 2) != 0;
+    constexpr bool NTC = (NT & 1) != 0;  // streaming stores for C
+    constexpr bool NTA = false;          // colidx/vals are read with plain loads (a streaming hint made no difference)
 
     __shared__ int s_raw[kWavesPerBlock * smem_ints_per_wave()];
     __shared__ float s_red[kWavesPerBlock * TW];

@@ -154,8 +154,9 @@ scorch_status_t hip_fail(hipError_t e, const char *what);
 scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                            hipStream_t stream);
 
-scorch_status_t launch_coo_rowptr(int32_t m, int64_t nnz, const int32_t *row_idx, int32_t *rowptr, int32_t *bad_flag,
-                                  hipStream_t stream);
+scorch_status_t launch_rowptr_from_keys(int32_t m, int64_t count, const int32_t *keys, const int32_t *pos,
+                                        bool strictly_increasing, int32_t *rowptr, int32_t *bad_flag,
+                                        hipStream_t stream);
 
 // spmm_exec.hip
 scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,

@@ -188,26 +188,34 @@ __global__ __launch_bounds__(kBlock) void plan_sorted_kernel(const int32_t *rowp
     }
 }
 
-// Row pointers of a row-sorted coordinate list: entry p closes the rows between its predecessor's row and its own.
-__global__ __launch_bounds__(kBlock) void coo_rowptr_kernel(const int32_t *row_idx, int64_t nnz, int32_t m,
-                                                            int32_t *rowptr, int32_t *bad_flag) {
-    for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p <= nnz; p += (int64_t)gridDim.x * kBlock) {
-        const int prev = p > 0 ? row_idx[p - 1] : -1;
-        const int cur = p < nnz ? row_idx[p] : m;
-        if (cur < prev || (p < nnz && (cur < 0 || cur >= m))) {
+// Row pointers from a sorted list of row keys.  Coordinate list: keys are the row coordinates of the entries and
+// position p itself is the pointer (pos == nullptr).  Doubly compressed rows: keys are the ids of the stored rows
+// and pos[p] is where row keys[p] starts (pos[count] = nnz).  Key p closes the rows between its predecessor and
+// itself: rowptr[r] = pos[p] for keys[p-1] < r <= keys[p]; the sentinel p = count closes the rows up to m.
+__global__ __launch_bounds__(kBlock) void rowptr_from_keys_kernel(const int32_t *keys, const int32_t *pos, int64_t count,
+                                                                  int32_t m, bool strictly_increasing, int32_t *rowptr,
+                                                                  int32_t *bad_flag) {
+    for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p <= count; p += (int64_t)gridDim.x * kBlock) {
+        const int prev = p > 0 ? keys[p - 1] : -1;
+        const int cur = p < count ? keys[p] : m;
+        const bool order_ok = strictly_increasing ? (cur > prev || p == 0) : cur >= prev;
+        if (!order_ok || (p < count && (cur < 0 || cur >= m))) {
             if (bad_flag) *bad_flag = 1;
             continue;
         }
-        for (int r = prev + 1; r <= cur; ++r) rowptr[r] = (int32_t)p;
+        const int32_t value = pos ? pos[p] : (int32_t)p;
+        for (int r = prev + 1; r <= cur; ++r) rowptr[r] = value;
     }
 }
 
-scorch_status_t launch_coo_rowptr(int32_t m, int64_t nnz, const int32_t *row_idx, int32_t *rowptr, int32_t *bad_flag,
-                                  hipStream_t stream) {
-    const uint32_t grid = (uint32_t)std::min<int64_t>((nnz + 1 + kBlock - 1) / kBlock, 256 * 32);
-    hipLaunchKernelGGL(coo_rowptr_kernel, dim3(grid), dim3(kBlock), 0, stream, row_idx, nnz, m, rowptr, bad_flag);
+scorch_status_t launch_rowptr_from_keys(int32_t m, int64_t count, const int32_t *keys, const int32_t *pos,
+                                        bool strictly_increasing, int32_t *rowptr, int32_t *bad_flag,
+                                        hipStream_t stream) {
+    const uint32_t grid = (uint32_t)std::min<int64_t>((count + 1 + kBlock - 1) / kBlock, 256 * 32);
+    hipLaunchKernelGGL(rowptr_from_keys_kernel, dim3(grid), dim3(kBlock), 0, stream, keys, pos, count, m,
+                       strictly_increasing, rowptr, bad_flag);
     hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return hip_fail(e, "launch coo_rowptr_kernel");
+    if (e != hipSuccess) return hip_fail(e, "launch rowptr_from_keys_kernel");
     return SCORCH_OK;
 }
 

@@ -5,7 +5,7 @@ import pytest
 import torch
 
 import paper_2405_16883_amd as sp
-from oracle import coo_rowptr_oracle
+from oracle import coo_rowptr_oracle, dcsr_rowptr_oracle
 from workloads import csr_from_row_lengths, make_scaled_config
 
 from gpu_util import DeviceProblem, check_against_oracle
@@ -52,3 +52,27 @@ def test_spmm_from_a_coordinate_list(cfg, scale):
     torch.cuda.synchronize()
     check_against_oracle(p, d.Cfull.cpu().numpy(), d.ldc, label=f"{p.name} from COO")
     plan.destroy()
+
+
+@pytest.mark.parametrize("lens", [[0] * 50, [7], [0, 0, 5, 0, 0, 0, 9, 0], [3] * 1000, [0] * 999 + [1], [4, 0, 0, 1]])
+def test_dcsr_rowptr(lens):
+    L = np.asarray(lens)
+    m = len(L)
+    ids = np.nonzero(L)[0].astype(np.int32)
+    pos = np.concatenate([[0], np.cumsum(L[ids])]).astype(np.int32)
+    out = torch.full((m + 1,), -5, dtype=torch.int32, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    sp.scorch_dcsr_to_csr_rowptr(m, torch.from_numpy(ids).to(DEV), torch.from_numpy(pos).to(DEV), out, flag)
+    torch.cuda.synchronize()
+    assert int(flag.item()) == 0
+    assert np.array_equal(out.cpu().numpy(), dcsr_rowptr_oracle(m, ids, pos))
+
+
+def test_dcsr_flags_repeated_or_unsorted_rows():
+    for ids in ([1, 1], [2, 1], [0, 7]):
+        out = torch.zeros(5, dtype=torch.int32, device=DEV)
+        flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+        sp.scorch_dcsr_to_csr_rowptr(4, torch.tensor(ids, dtype=torch.int32, device=DEV),
+                                     torch.tensor([0, 1, 2], dtype=torch.int32, device=DEV), out, flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 1

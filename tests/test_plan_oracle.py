@@ -72,3 +72,15 @@ def test_coo_rowptr_oracle_against_the_generators_own_row_pointers():
         assert np.array_equal(coo_rowptr_oracle(p.m, rows), p.rowptr)
     assert coo_rowptr_oracle(4, np.zeros(0, np.int32)).tolist() == [0, 0, 0, 0, 0]
     assert coo_rowptr_oracle(5, np.array([1, 1, 3], np.int32)).tolist() == [0, 0, 2, 2, 3, 3]
+
+
+def test_dcsr_rowptr_oracle_round_trip():
+    from oracle import dcsr_rowptr_oracle
+    for cfg, scale in ((3, 0.02), (4, 0.002)):
+        p = make_scaled_config(cfg, scale, seed=3)
+        L = p.row_lengths
+        ids = np.nonzero(L)[0]
+        pos = np.concatenate([[0], np.cumsum(L[ids])])
+        assert np.array_equal(dcsr_rowptr_oracle(p.m, ids, pos), p.rowptr)
+    assert dcsr_rowptr_oracle(5, np.array([1, 3]), np.array([0, 2, 3])).tolist() == [0, 0, 2, 2, 3, 3]
+    assert dcsr_rowptr_oracle(3, np.zeros(0, np.int64), np.array([0])).tolist() == [0, 0, 0, 0]
