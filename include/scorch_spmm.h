@@ -100,12 +100,13 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
                                  scorch_spmm_plan_t **plan_out);
 
 /*
- * Planned SpMM: same result contract as scorch_spmm_csr, executed through the plan's row lists
- * (one fused launch, plus one small fix-up launch when rows were split across workgroups, plus,
- * for wide B with few rows, a pre-pass that copies B into column-slice-major order so that each
- * accelerator die keeps its slice of B in its own L2).
- * Never waits, never allocates.  The partial rows live in the plan workspace, so two
- * executions of one plan must not overlap in time (same stream, or synchronise).
+ * Planned SpMM: same result contract as scorch_spmm_csr, executed through the plan's row lists:
+ * one fused launch, plus one small fix-up launch when rows were split across workgroups; for wide
+ * B with few rows a pre-pass first copies B into column-slice-major order so that each accelerator
+ * die keeps its slice of B in its own L2; matrices with a few percent of their entries stored and
+ * sorted rows go to a kernel that streams that copy of B through LDS instead of gathering.
+ * Never waits, never allocates.  The partial rows and the copy of B live in the plan workspace, so
+ * two executions of one plan must not overlap in time (same stream, or synchronise).
  */
 scorch_status_t scorch_spmm_csr_planned(const scorch_spmm_plan_t *plan,
                                         const int32_t *rowptr, const int32_t *colidx, const float *vals,
