@@ -92,3 +92,54 @@ def test_full_size_sampled_rows_and_row_sums(cfg):
     plan = d.make_plan()
     check_against_oracle(q, d.run_planned(plan), d.ldc, exact=True, rows=rows, label=f"workload {cfg} planned int")
     plan.destroy()
+
+
+def test_operands_beyond_two_to_the_31_elements():
+    """B and C with more than 2^31 elements each (64-bit addressing inside the kernels): m = k = 2^22 + 5, n = 520.
+    B is drawn on the device; the oracle sees a compact copy of the B rows that the sampled rows of A reference."""
+    from oracle import spmm_csr_oracle
+
+    dev = torch.device("cuda:0")
+    m = k = (1 << 22) + 5
+    n = 520
+    assert m * n > 2**31
+    rng = np.random.default_rng(31)
+    lens = np.full(m, 3, dtype=np.int64)
+    lens[rng.integers(0, m, size=1000)] = 0
+    lens[m - 2] = 3000  # a long row whose C row lies beyond element 2^31
+    lens[7] = 700
+    rowptr = np.zeros(m + 1, dtype=np.int64)
+    np.cumsum(lens, out=rowptr[1:])
+    nnz = int(rowptr[-1])
+    colidx = rng.integers(0, k, size=nnz, dtype=np.int64)
+    colidx[::5] = k - 1 - (colidx[::5] % 1000)  # many references to the last rows of B (beyond element 2^31)
+    vals = rng.uniform(-1, 1, size=nnz).astype(np.float32)
+    g = torch.Generator(device=dev).manual_seed(5)
+    B = torch.randn((k, n), generator=g, dtype=torch.float32, device=dev)
+    C = torch.full((m, n), -9.0, dtype=torch.float32, device=dev)
+    rp_d = torch.from_numpy(rowptr.astype(np.int32)).to(dev)
+    ci_d = torch.from_numpy(colidx.astype(np.int32)).to(dev)
+    va_d = torch.from_numpy(vals).to(dev)
+    rows = np.unique(np.concatenate([[0, 7, m - 2, m - 1], rng.integers(m - 100000, m, size=150),
+                                     rng.integers(0, m, size=150), np.nonzero(lens == 0)[0][:10]]))
+
+    def check(label):
+        torch.cuda.synchronize()
+        # compact problem for the oracle: only the sampled rows and the B rows they touch
+        seg = [np.arange(rowptr[i], rowptr[i + 1]) for i in rows]
+        idx = np.concatenate(seg)
+        cols, inv = np.unique(colidx[idx], return_inverse=True)
+        Bsub = B[torch.from_numpy(cols).to(dev)].cpu().numpy()
+        rp = np.concatenate([[0], np.cumsum([len(s) for s in seg])]).astype(np.int32)
+        C_ref, T = spmm_csr_oracle(len(rows), n, rp, inv.astype(np.int32), vals[idx], Bsub)
+        got = C[torch.from_numpy(rows).to(dev)].cpu().numpy().astype(np.float64)
+        bad = ~(np.abs(got - C_ref) <= RTOL_T * T + ATOL)
+        assert not bad.any(), f"{label}: {int(bad.sum())} sampled elements out of tolerance"
+
+    plan = sp.scorch_spmm_plan(m, k, n, rp_d, nnz, colidx=ci_d)
+    sp.scorch_spmm_csr_planned(plan, rp_d, ci_d, va_d, B, C)
+    check("planned")
+    plan.destroy()
+    C.fill_(-9.0)
+    sp.scorch_spmm_csr(m, k, n, rp_d, ci_d, va_d, B, C)
+    check("plan-free")
