@@ -159,6 +159,18 @@ def cpu_baseline_and_check(res, torch, target_nnz=80_000_000):
     t0 = time.perf_counter()
     C_ref, _ = spmm_csr_oracle(p.m, p.n, p.rowptr, p.colidx, p.vals, p.B, p.ldb, rows=rows, want_T=False)
     dt = time.perf_counter() - t0
+    # the same rows again, split into contiguous chunks over the host cores (each chunk is the same serial loop,
+    # so the result is bit-identical); ctypes releases the GIL during the call
+    from concurrent.futures import ThreadPoolExecutor
+    cores = max(1, min(16, len(os.sched_getaffinity(0))))
+    chunks = [c for c in np.array_split(rows, cores) if len(c)]
+    t0 = time.perf_counter()
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        parts = list(pool.map(lambda c: spmm_csr_oracle(p.m, p.n, p.rowptr, p.colidx, p.vals, p.B, p.ldb, rows=c,
+                                                        want_T=False)[0], chunks))
+    dt_par = time.perf_counter() - t0
+    same = bool(np.array_equal(np.concatenate(parts), C_ref))
+    del parts
     # parity on the sample (tolerance needs T; computed outside the timed part)
     _, T = spmm_csr_oracle(p.m, p.n, p.rowptr, p.colidx, p.vals, p.B, p.ldb, rows=rows[: min(len(rows), 20000)])
     C_gpu = res.C[start:start + T.shape[0]].cpu().numpy().astype(np.float64)
@@ -170,6 +182,8 @@ def cpu_baseline_and_check(res, torch, target_nnz=80_000_000):
         "kind": "oracle",
         "sample": f"rows [{start},{stop}) of the same workload: {sample_nnz} nnz, n={p.n}, {dt:.2f} s serial fp64",
         "gpu_matches_oracle_on_sample": ok,
+        "all_cores": {"value": 2.0 * sample_nnz * p.n / dt_par / 1e9, "unit": "GFLOP/s", "cores": len(chunks),
+                      "seconds": dt_par, "bit_identical_to_serial": same},
     }
 
 
@@ -271,7 +285,8 @@ def main():
     }
     cpu = None if args.no_cpu else cpu_baseline_and_check(res, torch)
     if cpu is not None:
-        log(f"[bench] cpu oracle: {cpu['value']:.2f} GFLOP/s on 1 core; GPU matches on sample: {cpu['gpu_matches_oracle_on_sample']}")
+        log(f"[bench] cpu oracle: {cpu['value']:.2f} GFLOP/s on 1 core, {cpu['all_cores']['value']:.2f} GFLOP/s on "
+            f"{cpu['all_cores']['cores']} cores; GPU matches on sample: {cpu['gpu_matches_oracle_on_sample']}")
     del res
     others = {}
     if not args.no_others:
@@ -309,6 +324,7 @@ def main():
         "config": {"workload": name, "m": head["m"], "k": head["k"], "n": head["n"], "nnz": head["nnz"],
                    "seed": args.seed, "plan": head["plan"], "plan_ms": head["plan_ms"]},
         "plan_free_ms_per_step": head["plan_free_event_ms_mean"],
+        "plan_amortised_in_steps": head["plan_ms"] / head["event_ms_mean"],
         "hbm_gbs_min_traffic": head["gbs_min_traffic"],
         "hbm_frac_of_peak": head["frac_hbm"],
         "cold_cache": {"event_ms_mean": head.get("cold_event_ms_mean"), "frac_hbm": head.get("cold_frac_hbm")},
