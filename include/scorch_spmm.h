@@ -86,8 +86,9 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * `workspace` (device, 256-byte aligned, at least the bound above) receives the row lists and
  * holds the partial rows at execution; it must stay allocated and unmodified while the plan
  * lives.  `colidx` may be NULL; when given (device, nnz entries) it is only inspected to see whether
- * every row stores its columns in non-decreasing order, which is what the panel kernel for
- * dense-ish matrices needs (with NULL, or with unsorted rows, the gather kernels are used).  The
+ * every row stores its columns in strictly increasing order, which is what the panel kernel for
+ * dense-ish matrices needs (with NULL, or with unsorted or repeated columns in a row, the gather
+ * kernels are used).  The
  * call enqueues on `stream` and WAITS for it (it reads nnz and the list sizes back).  The plan is valid for exactly this rowptr content
  * and this n, on the device that was current.
  * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=.."
@@ -104,7 +105,8 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
  * one fused launch, plus one small fix-up launch when rows were split across workgroups; for wide
  * B with few rows a pre-pass first copies B into column-slice-major order so that each accelerator
  * die keeps its slice of B in its own L2; matrices with a few percent of their entries stored and
- * sorted rows go to a kernel that streams that copy of B through LDS instead of gathering.
+ * strictly increasing columns in every row go to a kernel that streams that copy of B through LDS
+ * instead of gathering.
  * Never waits, never allocates.  The partial rows and the copy of B live in the plan workspace, so
  * two executions of one plan must not overlap in time (same stream, or synchronise).
  */

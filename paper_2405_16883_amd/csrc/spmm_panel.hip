@@ -5,15 +5,16 @@
 // by ~10 % of the rows of A, so it is cheaper to stream B through LDS once per block of rows and let
 // every row pick its entries out of LDS.  The loop order of the paper (rows, stored entries, dense
 // columns innermost and tiled) is kept per wavefront; what is added is a tiling of the *sparse* index j
-// into panels of 64 B rows -- which the paper avoids on CPUs because it needs a search in the sparse
-// level (Section 4.2).  Here the search is free: columns inside a row are sorted (checked by the
-// planner), every wavefront keeps a 64-entry register window of each of its rows (one entry per lane),
-// and the entries that fall into the current panel are the next few lanes of that window, found with
-// one ballot.  Entries reach the ALU by v_readlane (scalar broadcast), B values by ds_read_b128.
+// into panels of 32 or 64 B rows -- which the paper avoids on CPUs because it needs a search in the
+// sparse level (Section 4.2).  Here the search is free: columns inside a row are strictly increasing
+// (checked by the planner), every wavefront keeps a 64-entry register window of each of its rows (one
+// entry per lane), and the entries that fall into the current panel are the next few lanes of that
+// window, found with one ballot.  Entries reach the ALU by v_readlane (scalar broadcast), B values by
+// ds_read_b128.
 //
-//   workgroup = 16 wavefronts = 64 rows x one 256-column tile of C
-//   wavefront = 4 rows, lane l owns columns 4l..4l+3 of the tile, accumulators stay in registers
-//   panel     = 64 rows x 256 columns of B (64 KB of LDS), read from a tile-major copy of B
+//   workgroup = 16 wavefronts = 64 rows x one tile of C (256 or 512 columns), one workgroup per CU
+//   wavefront = 4 rows, lane l owns columns 4l..4l+3 (and 256+4l.. for the wide tile), accumulators in registers
+//   panel     = 64 KB of a tile-major copy of B (64 rows x 256 columns or 32 rows x 512 columns), two in LDS
 // Column tiles are dealt to the XCDs (tile_of_workgroup) so that the workgroups that walk the same
 // tile of B run on the same die, start together and find the panels in that die's L2.
 #include "spmm_internal.h"
@@ -24,25 +25,116 @@ namespace scorch {
 
 typedef float f4 __attribute__((ext_vector_type(4)));
 
-// RW rows per wavefront, WPB wavefronts per workgroup, kBatch LDS reads in flight per row and panel,
-// Q float4 per lane: the tile is 256*Q columns wide and a panel holds 64/Q rows of B (64 KB of LDS).
-template <int RW, int WPB, int kBatch, int Q>
-__global__ __launch_bounds__(WPB * kWave) void spmm_panel_kernel(const PanelArgs a) {
-    constexpr int kRowQuads = Q * (kPanelCols / 4);  // float4 per LDS row
-    constexpr int kRows = kPanelRows / Q;            // B rows per panel
-    __shared__ f4 s_b[kRows * kRowQuads];
+// Template parameters: RW rows per wavefront, kBatch entries whose LDS reads are in flight together, Q float4 per
+// lane (the tile is 256*Q columns wide), KR rows of B per panel (KR * Q KB of LDS, 64 KB in both shapes used).
+//
+// The panel is double-buffered: one 1024-thread workgroup per CU holds two panels in LDS.  The next panel is
+// fetched straight from global memory into LDS (global_load_lds_dwordx4: no registers, no ds_write) while the
+// wavefronts work on the current one, and one barrier per panel both publishes the fetched panel and retires
+// the one before it.  A workgroup covers 16*RW rows, so B crosses L2 -> LDS m/(16*RW) times.
+template <int Q, int KR>
+__device__ __forceinline__ void panel_fetch(const f4 *Bt, int k, int k0, f4 *sbuf, int wv, int lane) {
+    constexpr int kRowQuads = Q * (kPanelCols / 4);
+    const int64_t q0 = (int64_t)k0 * kRowQuads, qend = (int64_t)k * kRowQuads;
+    // the panel is one contiguous range of the tile: KR * Q chunks of 1 KB, dealt to the 16 wavefronts; a chunk
+    // is half a row or a row of B, so it lies wholly inside or wholly outside the tile
+#pragma unroll
+    for (int c = 0; c < KR * Q / 16; ++c) {
+        const int chunk = c * 16 + wv;
+        const int64_t g = q0 + chunk * 64;
+        if (g < qend) __builtin_amdgcn_global_load_lds(Bt + g + lane, sbuf + chunk * 64, 16, 0, 0);
+    }
+}
+
+template <int RW, int kBatch, int Q>
+struct PanelRows {
+    int pend[RW], wbase[RW], pos[RW], colreg[RW], colnext[RW];
+    float valreg[RW], valnext[RW];
+    f4 acc[RW][Q];
+};
+
+// One panel's worth of work for the RW rows of a wavefront.  Columns within a row are strictly increasing
+// (checked by the planner), so a panel of kRows rows of B takes at most kRows entries of a row: they are the
+// lanes [pos, lim) of the row's 64-entry window.  A window that would be left with fewer than kRows entries is
+// replaced: the replacement is requested before the panel's work and installed after it, so that its latency is
+// hidden behind the work.  The visits of all RW rows are issued together (LDS reads first, multiply-adds after)
+// to give a wavefront several independent reads per wait.
+template <int RW, int kBatch, int Q, int KR>
+__device__ __forceinline__ void panel_compute(PanelRows<RW, kBatch, Q> &st, const f4 *sbuf, int k0, int lane,
+                                              const int32_t *colidx, const float *vals) {
+    constexpr int kRowQuads = Q * (kPanelCols / 4);
+    constexpr int kRows = KR;
+    const int kend = k0 + kRows;
+    int lim[RW], j[RW];
+    bool shift[RW];
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        lim[r] = __builtin_popcountll(__ballot(st.colreg[r] < kend));
+        j[r] = st.pos[r];
+        shift[r] = lim[r] > kWave - kRows && st.wbase[r] + lim[r] < st.pend[r];
+        if (shift[r]) {
+            const int p = st.wbase[r] + lim[r] + lane;
+            st.colnext[r] = p < st.pend[r] ? colidx[p] : INT_MAX;
+            st.valnext[r] = p < st.pend[r] ? vals[p] : 0.f;
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        for (int jj = j[r]; jj < lim[r]; jj += kBatch) {
+            // issue the LDS reads of a whole batch first, then the multiply-adds; all branches are
+            // wave-uniform (scalar), entries past lim are skipped
+            f4 x[kBatch][Q];
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                if (jj + u < lim[r]) {
+                    const int c = __builtin_amdgcn_readlane(st.colreg[r], jj + u);
+#pragma unroll
+                    for (int q = 0; q < Q; ++q) x[u][q] = sbuf[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < kBatch; ++u) {
+                if (jj + u < lim[r]) {
+                    const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.valreg[r]), jj + u));
+#pragma unroll
+                    for (int q = 0; q < Q; ++q)
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) st.acc[r][q][i] = __builtin_fmaf(v, x[u][q][i], st.acc[r][q][i]);
+                }
+            }
+        }
+    }
+#pragma unroll
+    for (int r = 0; r < RW; ++r) {
+        if (shift[r]) {
+            st.wbase[r] += lim[r];
+            st.colreg[r] = st.colnext[r];
+            st.valreg[r] = st.valnext[r];
+            st.pos[r] = 0;
+        } else {
+            st.pos[r] = lim[r];
+        }
+    }
+}
+
+template <int RW, int kBatch, int Q, int KR>
+__global__ __launch_bounds__(16 * kWave) void spmm_panel_kernel(const PanelArgs a) {
+    constexpr int WPB = 16;
+    constexpr int kRowQuads = Q * (kPanelCols / 4);
+    constexpr int kRows = KR;
+    __shared__ f4 s_b0[kRows * kRowQuads];
+    __shared__ f4 s_b1[kRows * kRowQuads];
     const int tid = threadIdx.x;
-    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform: keeps the row state in SGPRs
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lane = tid & 63;
     uint32_t ct, rb;
     if (!tile_of_workgroup(a.xcd_slices, a.ntiles, (uint32_t)a.nrb, ct, rb)) return;
-    const int c0 = (int)ct * (Q * kPanelCols) + lane * 4;  // lane owns columns c0 + 256 q .. +3, q < Q
+    const int c0 = (int)ct * (Q * kPanelCols) + lane * 4;
     const f4 *Bt = reinterpret_cast<const f4 *>(a.Bp + (int64_t)ct * a.k * (Q * kPanelCols));
     const int64_t row_base = (int64_t)rb * (WPB * RW) + wv * RW;
 
-    int pend[RW], wbase[RW], pos[RW], colreg[RW];
-    float valreg[RW];
-    f4 acc[RW][Q];
+    panel_fetch<Q, KR>(Bt, a.k, 0, s_b0, wv, lane);
+    PanelRows<RW, kBatch, Q> st;
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
         const int64_t row = row_base + r;
@@ -51,63 +143,26 @@ __global__ __launch_bounds__(WPB * kWave) void spmm_panel_kernel(const PanelArgs
             p0 = a.rowptr[row];
             p1 = a.rowptr[row + 1];
         }
-        wbase[r] = p0;
-        pend[r] = p1;
-        pos[r] = 0;
+        st.wbase[r] = p0;
+        st.pend[r] = p1;
+        st.pos[r] = 0;
         const int p = p0 + lane;
-        colreg[r] = p < p1 ? a.colidx[p] : INT_MAX;
-        valreg[r] = p < p1 ? a.vals[p] : 0.f;
+        st.colreg[r] = p < p1 ? a.colidx[p] : INT_MAX;
+        st.valreg[r] = p < p1 ? a.vals[p] : 0.f;
+        st.colnext[r] = INT_MAX;
+        st.valnext[r] = 0.f;
 #pragma unroll
-        for (int q = 0; q < Q; ++q) acc[r][q] = f4{0.f, 0.f, 0.f, 0.f};
+        for (int q = 0; q < Q; ++q) st.acc[r][q] = f4{0.f, 0.f, 0.f, 0.f};
     }
-
-    for (int k0 = 0; k0 < a.k; k0 += kRows) {
-        __syncthreads();  // everyone is done with the previous panel
-        const int quads = min(kRows, a.k - k0) * kRowQuads;
-        const f4 *src = Bt + (int64_t)k0 * kRowQuads;
-        for (int i = tid; i < quads; i += WPB * kWave) s_b[i] = src[i];
-        __syncthreads();
-        const int kend = k0 + kRows;
-#pragma unroll
-        for (int r = 0; r < RW; ++r) {
-            while (true) {
-                // columns are sorted: the entries of this window below kend are its first `lim` lanes
-                const int lim = __builtin_popcountll(__ballot(colreg[r] < kend));
-                for (int j = pos[r]; j < lim; j += kBatch) {
-                    // issue the LDS reads of a whole batch first, then the multiply-adds; all branches are
-                    // wave-uniform (scalar), entries past `lim` are skipped
-                    f4 x[kBatch][Q];
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        if (j + u < lim) {
-                            const int c = __builtin_amdgcn_readlane(colreg[r], j + u);
-#pragma unroll
-                            for (int q = 0; q < Q; ++q) x[u][q] = s_b[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
-                        }
-                    }
-#pragma unroll
-                    for (int u = 0; u < kBatch; ++u) {
-                        if (j + u < lim) {
-                            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(valreg[r]), j + u));
-#pragma unroll
-                            for (int q = 0; q < Q; ++q)
-#pragma unroll
-                                for (int i = 0; i < 4; ++i) acc[r][q][i] = __builtin_fmaf(v, x[u][q][i], acc[r][q][i]);
-                        }
-                    }
-                }
-                pos[r] = lim;
-                if (lim == kWave && wbase[r] + kWave < pend[r]) {
-                    // window used up and the row goes on: slide it
-                    wbase[r] += kWave;
-                    const int p = wbase[r] + lane;
-                    colreg[r] = p < pend[r] ? a.colidx[p] : INT_MAX;
-                    valreg[r] = p < pend[r] ? a.vals[p] : 0.f;
-                    pos[r] = 0;
-                } else {
-                    break;
-                }
-            }
+    for (int k0 = 0; k0 < a.k; k0 += 2 * kRows) {
+        __syncthreads();  // panel k0 has landed in s_b0; nobody reads s_b1 any more
+        const bool odd = k0 + kRows < a.k;
+        if (odd) panel_fetch<Q, KR>(Bt, a.k, k0 + kRows, s_b1, wv, lane);
+        panel_compute<RW, kBatch, Q, KR>(st, s_b0, k0, lane, a.colidx, a.vals);
+        if (odd) {
+            __syncthreads();  // panel k0 + kRows has landed in s_b1; nobody reads s_b0 any more
+            if (k0 + 2 * kRows < a.k) panel_fetch<Q, KR>(Bt, a.k, k0 + 2 * kRows, s_b0, wv, lane);
+            panel_compute<RW, kBatch, Q, KR>(st, s_b1, k0 + kRows, lane, a.colidx, a.vals);
         }
     }
 #pragma unroll
@@ -117,7 +172,7 @@ __global__ __launch_bounds__(WPB * kWave) void spmm_panel_kernel(const PanelArgs
         for (int q = 0; q < Q; ++q) {
             const int c = c0 + q * kPanelCols;
             if (row < a.m && c < a.n) {
-                f4 v = acc[r][q];
+                f4 v = st.acc[r][q];
                 if (a.bias)
 #pragma unroll
                     for (int i = 0; i < 4; ++i) v[i] += a.bias[c + i];
@@ -138,12 +193,12 @@ bool panel_operands_ok(int32_t n, const float *B, int64_t ldb, const float *C, i
 scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                              const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                              const float *bias, int32_t act, hipStream_t stream) {
-    // Shapes (rows per wavefront / wavefronts per workgroup / float4 per lane).  Both keep 8 wavefronts per SIMD
-    // resident (<= 64 VGPRs, two 1024-thread workgroups per CU), which is what hides the LDS and scalar latencies:
-    // a 4-wavefront, 16-rows-per-wavefront shape of the same kernel ran 2.1x slower.
+    // Two shapes: tile of 256 columns with 64-row panels, or tile of 512 columns with 32-row panels (the wide
+    // tile halves the per-entry broadcast overhead and is chosen for denser matrices and n >= 512).  Both use
+    // 64 rows per workgroup and 128 KB of LDS, i.e. one workgroup and four wavefronts per SIMD on a CU.
     const int variant = plan->params.PANEL;
     struct Shape { int RW, WPB, Q; };
-    const Shape sh = variant == 2 ? Shape{2, 16, 2} : Shape{4, 16, 1};
+    const Shape sh = variant == 2 ? Shape{4, 16, 2} : Shape{4, 16, 1};
     const int W = sh.Q * kPanelCols;
     float *Bp = reinterpret_cast<float *>(plan->workspace + plan->layout.off_bpack);
     scorch_status_t st = launch_pack_b(B, ldb, plan->k, plan->n, W, Bp, stream);
@@ -169,8 +224,8 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
         return SCORCH_ERR_UNSUPPORTED;
     }
     const dim3 g((uint32_t)grid), b(sh.WPB * kWave);
-    if (variant == 2) hipLaunchKernelGGL((spmm_panel_kernel<2, 16, 2, 2>), g, b, 0, stream, a);
-    else hipLaunchKernelGGL((spmm_panel_kernel<4, 16, 4, 1>), g, b, 0, stream, a);
+    if (variant == 2) hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 32>), g, b, 0, stream, a);
+    else hipLaunchKernelGGL((spmm_panel_kernel<4, 4, 1, 64>), g, b, 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "launch spmm_panel_kernel");
     return SCORCH_OK;

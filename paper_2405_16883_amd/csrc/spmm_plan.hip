@@ -175,7 +175,7 @@ __global__ __launch_bounds__(kBlock) void plan_window_kernel(const int32_t *rowp
     win_row_start[w] = (int32_t)lo;
 }
 
-// Sets *flag when some row stores a column index smaller than its predecessor (one wavefront per row).
+// Sets *flag when some row's column indices are not strictly increasing (one wavefront per row).
 __global__ __launch_bounds__(kBlock) void plan_sorted_kernel(const int32_t *rowptr, const int32_t *colidx, int32_t m,
                                                              int32_t *flag) {
     const int lane = threadIdx.x & 63;
@@ -183,7 +183,7 @@ __global__ __launch_bounds__(kBlock) void plan_sorted_kernel(const int32_t *rowp
          row += (int64_t)gridDim.x * kWavesPerBlock) {
         const int p0 = rowptr[row], p1 = rowptr[row + 1];
         bool bad = false;
-        for (int p = p0 + 1 + lane; p < p1; p += kWave) bad |= colidx[p] < colidx[p - 1];
+        for (int p = p0 + 1 + lane; p < p1; p += kWave) bad |= colidx[p] <= colidx[p - 1];
         if (bad) *flag = 1;
     }
 }
@@ -264,17 +264,17 @@ static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
     return slice_bytes <= kL2SliceBudget && b_bytes > kL2SliceBudget && nnz / m >= 32;
 }
 
-// The panel kernel (spmm_panel.hip) streams all of B through LDS once per block of rows of A, a cost that does
+// The panel kernel (spmm_panel.hip) streams all of B through LDS once per block of 64 rows of A, a cost that does
 // not depend on nnz, and then pays per entry about 40 % less than the gather kernels.  Measured on 4096 x 16384
-// weights with n = 2048 it wins from about 4 % stored entries upwards (5 %: 0.99 against 1.26 ms, 10 %: 1.45 against
-// 2.29 ms, 50 %: 4.2 against 11.7 ms) and loses below (2.5 %: 0.77 against 0.70 ms); with fewer than two workgroups
-// per CU (64 rows x 256 columns each) it loses at any density.  Returns the kernel shape (0 = do not use).
+// weights with n = 2048 it wins from about 4 % stored entries upwards and loses below (2.5 %: 0.77 against 0.70 ms);
+// it needs a workgroup (64 rows x 256 or 512 columns) for every CU: with 128 blocks of 64 x 256 it loses at any
+// density, with 256 it wins by 15 %.  Returns the kernel shape (0 = do not use).
 static int32_t want_panel(int32_t m, int32_t k, int64_t nnz, int32_t n) {
     if (m <= 0 || k < 1024 || n % 4 != 0 || n < kPanelCols) return 0;
     const double density = (double)nnz / ((double)m * (double)k);
     const int64_t tasks = (int64_t)((m + 63) / 64) * ((n + kPanelCols - 1) / kPanelCols);
-    if (density < 0.04 || nnz / m < 128 || tasks < 512) return 0;
-    return (density >= 0.08 && n >= 2 * kPanelCols) ? 2 : 1;  // 2: 512-column tiles, 32 rows per workgroup
+    if (density < 0.04 || nnz / m < 128 || tasks < 256) return 0;
+    return (density >= 0.08 && n >= 2 * kPanelCols && tasks >= 512) ? 2 : 1;  // 2: 512-column tiles
 }
 
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t) {
@@ -357,7 +357,7 @@ scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, cons
     char *ws = plan->workspace;
     int32_t totals[kQ] = {0, 0, 0, 0, 0};
     int32_t unsorted = 0;
-    // The panel kernel needs every row's columns in non-decreasing order; without colidx this cannot be
+    // The panel kernel needs every row's columns in strictly increasing order; without colidx this cannot be
     // verified, so the mode is dropped.
     if (plan->params.PANEL && (!colidx || plan->m == 0 || plan->nnz == 0)) plan->params.PANEL = 0;
     if (plan->params.PANEL) {

@@ -124,9 +124,13 @@ def test_panel_kernel_forced(m, k, n, shape):
         q = integer_valued(p, seed=n)
         run_both(q, exact=True, label=f"panel int {m}x{k}x{n}")
         run_both(with_padding(p, n + 4), ldc=n + 12, label=f"panel padded {m}x{k}x{n}")
-        # sorted rows that repeat a column are fine too
+        # sorted rows that repeat a column are not for the panel kernel: the planner must hand them to the gather kernels
         r = csr_from_row_lengths(np.minimum(lens * 2, 3 * k), k, n, seed=m + 1, duplicates=True, sorted_cols=True)
-        run_both(r, label=f"panel duplicates {m}x{k}x{n}")
+        d = DeviceProblem(r)
+        plan = d.make_plan()
+        assert plan.info().mode != 2
+        check_against_oracle(r, d.run_planned(plan), d.ldc, label=f"panel duplicates {m}x{k}x{n}")
+        plan.destroy()
 
 
 def test_panel_mode_is_dropped_for_unsorted_rows_or_missing_colidx():
