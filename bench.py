@@ -26,6 +26,7 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+PLAIN_FMA_TFLOPS = 78.6  # fp32 vector rate without packed operations: 256 CUs x 64 lanes x 2 flop x 2.4 GHz
 HEADLINE_CONFIG = 4  # large power-law graph aggregation: the largest single-GPU workload, HBM-bound
 
 
@@ -255,7 +256,17 @@ def main():
                     "bytes_min": bytes_min, "plan_ms": res.plan_ms,
                     "plan": {"BN": info.BN, "ALPHA": info.ALPHA, "LW": info.LW, "CH": info.CH, "BCH": info.BCH,
                              "windows": info.n_windows, "short_rows": info.n_short_rows, "wave_rows": info.n_wave_rows,
-                             "items": info.n_items, "split_rows": info.n_split_rows}})
+                             "items": info.n_items, "split_rows": info.n_split_rows,
+                             "mode": {0: "gather", 1: "xcd_sliced_gather", 2: "lds_panel"}[info.mode]}})
+        out["mode"] = out["plan"]["mode"]
+        tr_ = traffic.get(CONFIG_NAMES[cfg])
+        if tr_:
+            out["traffic"] = tr_["total_bytes"]
+        if info.mode == 2:
+            # the panel kernel is bound by plain fp32 multiply-adds out of LDS, not by HBM: price it against the
+            # chip's v_fma_f32 rate without packed operations (256 CUs x 64 lanes x 2 flop x 2.4 GHz)
+            out["alu_roofline"] = {"bound": "alu", "achieved": out["gflops"] / 1e3, "peak": PLAIN_FMA_TFLOPS,
+                                   "unit": "TFLOP/s", "frac": out["gflops"] / 1e3 / PLAIN_FMA_TFLOPS}
         log(f"[bench] cfg {cfg}: {out['event_ms_mean']:.4f} ms/step  {out['gflops']:.0f} GFLOP/s  "
             f"{out['gbs_min_traffic']:.0f} GB/s min-traffic = {100 * out['frac_hbm']:.1f}% of HBM peak  (plan {res.plan_ms:.2f} ms)")
         return res, out
@@ -271,7 +282,8 @@ def main():
     tr = traffic.get(name)
     roofline = {
         "bound": "hbm",
-        "kernel": "spmm_fused_kernel (+ spmm_fixup_kernel, same events)",
+        "kernel": ("spmm_panel_kernel (+ spmm_pack_b_kernel, same events)" if head["plan"]["mode"] == "lds_panel"
+                   else "spmm_fused_kernel (+ spmm_fixup_kernel, same events)"),
         "achieved": head["gbs_min_traffic"],
         "peak": HBM_PEAK_GBS,
         "unit": "GB/s",
@@ -305,6 +317,7 @@ def main():
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
                                                            "gbs_min_traffic", "frac_hbm", "cold_event_ms_mean",
                                                            "cold_frac_hbm", "plan_ms", "plan_free_event_ms_mean") + (("sddmm",) if "sddmm" in o else ())
+                                        + tuple(x for x in ("mode", "traffic", "alu_roofline") if x in o)
                                         + (("graph_replay_ms_per_step",) if "graph_replay_ms_per_step" in o else ())}
             del r
 
