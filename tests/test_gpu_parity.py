@@ -133,6 +133,24 @@ def test_panel_kernel_forced(m, k, n, shape):
         plan.destroy()
 
 
+@pytest.mark.parametrize("shape", [1, 2])
+@pytest.mark.parametrize("k", [1, 31, 32, 33, 64, 65, 200])
+def test_panel_kernel_fully_dense_rows(k, shape):
+    """Every row stores all k columns: each panel takes a whole 32- or 64-entry stretch of a row's register window,
+    so the window is replaced at every panel; k around the panel heights covers the ragged last panel."""
+    m, n = 70, 516
+    lens = np.full(m, k)
+    lens[[3, 69]] = 0
+    p = csr_from_row_lengths(lens, k, n, seed=k, duplicates=False)
+    with tuning(f"panel={shape}"):
+        d = DeviceProblem(p)
+        plan = d.make_plan()
+        assert plan.info().mode == 2
+        check_against_oracle(p, d.run_planned(plan), d.ldc, label=f"panel dense k={k}")
+        plan.destroy()
+        run_both(integer_valued(p, seed=k), exact=True, label=f"panel dense int k={k}")
+
+
 def test_panel_mode_is_dropped_for_unsorted_rows_or_missing_colidx():
     p = csr_from_row_lengths([40] * 600, 300, 256, seed=3, sorted_cols=False)
     with tuning("panel=1"):
