@@ -108,6 +108,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
 
     __shared__ int s_raw[kWavesPerBlock * smem_ints_per_wave()];
     __shared__ float s_red[kWavesPerBlock * TW];
+    // one-lane groups (n <= 4) only: the products of a window's entries, summed per row afterwards
+    __shared__ __attribute__((aligned(16))) float s_prod[G == 1 ? kWavesPerBlock * kStageMax * V : 1];
 
     const int tid = threadIdx.x;
     const int wv = tid >> 6;
@@ -211,6 +213,40 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     const int sbeg = __shfl(rpv, first, kWave);
     const int send = __shfl(rnext, last, kWave);
     const int cnt = min(send - sbeg, kStageMax);
+    if constexpr (G == 1) {
+        // SpMV and its neighbours (n <= 4, one lane per entry): a window has far fewer rows than the wavefront has
+        // lanes, so the lanes split the window's *entries* instead of its rows: every lane reads its entries
+        // (coalesced), gathers the V values of B they point at, and parks the products in LDS; then the lane of
+        // each short row adds up that row's products in stored order.
+        vec *prod = reinterpret_cast<vec *>(s_prod) + wv * kStageMax;
+        constexpr int kSteps = (kStageMax + kWave - 1) / kWave;
+        vec x[kSteps];
+        float v[kSteps];
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            const int e = lane + i * kWave;
+            const bool ok = e < cnt;
+            const int c = ok ? a.colidx[sbeg + e] : 0;
+            v[i] = ok ? a.vals[sbeg + e] : 0.f;
+            x[i] = ok ? vload<V>(Bc + (int64_t)c * a.ldb) : vzero<V>();
+        }
+#pragma unroll
+        for (int i = 0; i < kSteps; ++i) {
+            const int e = lane + i * kWave;
+            if (e < cnt) {
+                vec pr = vzero<V>();
+                vfma<V>(pr, v[i], x[i]);
+                prod[e] = pr;
+            }
+        }
+        wave_lds_sync();
+        if (is_short) {
+            for (int q = rpv - sbeg; q < rnext - sbeg; ++q) vadd<V>(acc[0], prod[q]);
+            vstore<V, NTC>(a.C + (int64_t)(r0 + lane) * a.ldc + c0,
+                           apply_epilogue<V>(acc[0], a.bias ? a.bias + c0 : nullptr, a.act));
+        }
+        return;
+    }
     for (int e = lane; e < cnt; e += kWave) {
         lcol[e] = ld_idx<NTA>(a.colidx + sbeg + e);
         lval[e] = ld_val<NTA>(a.vals + sbeg + e);
