@@ -62,6 +62,25 @@ def test_epilogue_column_counts_and_split_rows(n):
     run_epilogue(p, bias, False, exact=True, label=f"n={n} no act", tune="ch=128,bch=256")
 
 
+@pytest.mark.parametrize("tune", [None, "bn=256,lw=64", "bn=256,lw=32,ch=64", "bn=128,lw=8"])
+@pytest.mark.parametrize("n", [1, 2, 4])
+def test_one_lane_groups_split_the_entries_of_a_window(n, tune):
+    """n <= 4: the lanes of a wavefront take the entries of a window and each row's lane adds up its products.
+    Many short rows of every length up to the window limit, medium rows in between (their entries lie inside the
+    staged span but belong to another path), empty rows, one long row; with and without bias and ReLU."""
+    rng = np.random.default_rng(7 * n)
+    lens = rng.integers(0, 66, size=3000)
+    lens[rng.integers(0, 3000, size=200)] = 0
+    lens[rng.integers(0, 3000, size=40)] = rng.integers(65, 300, size=40)
+    lens[1234] = 5000
+    p = csr_from_row_lengths(lens, 6000, n, seed=n, duplicates=False)
+    bias = rng.standard_normal(n).astype(np.float32)
+    run_epilogue(p, None, False, label=f"n={n} plain [{tune}]", tune=tune)
+    run_epilogue(p, bias, True, label=f"n={n} bias relu [{tune}]", tune=tune)
+    q = integer_valued(p, seed=n)
+    run_epilogue(q, rng.integers(-9, 10, size=n).astype(np.float32), True, exact=True, label=f"n={n} int [{tune}]", tune=tune)
+
+
 def test_epilogue_full_size_gcn_layer():
     p = make_config(3, seed=0)
     bias = np.random.default_rng(2).standard_normal(p.n).astype(np.float32) * 0.1
