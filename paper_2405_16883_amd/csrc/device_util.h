@@ -9,6 +9,10 @@ template <int V> struct Vec;
 template <> struct Vec<1> { using type = float; };
 template <> struct Vec<2> { typedef float type __attribute__((ext_vector_type(2))); };
 template <> struct Vec<4> { typedef float type __attribute__((ext_vector_type(4))); };
+// The same vectors at float alignment: gfx950 takes a global_load/store_dwordx4 at any 4-byte aligned address, so a
+// row of B or C that is not 16-byte aligned (odd n or leading dimension) can still move four floats per lane.
+template <int V> struct VecU { using type = typename Vec<V>::type; };
+template <> struct VecU<4> { typedef float type __attribute__((ext_vector_type(4), aligned(4))); };
 
 template <int V> __device__ __forceinline__ typename Vec<V>::type vzero() {
     typename Vec<V>::type z;
@@ -52,13 +56,20 @@ template <int V, int OFF> __device__ __forceinline__ typename Vec<V>::type vlane
     }
     return r;
 }
-template <int V> __device__ __forceinline__ typename Vec<V>::type vload(const float *p) {
-    return *reinterpret_cast<const typename Vec<V>::type *>(p);
+template <int V, bool UA = false> __device__ __forceinline__ typename Vec<V>::type vload(const float *p) {
+    if constexpr (UA) return *reinterpret_cast<const typename VecU<V>::type *>(p);
+    else return *reinterpret_cast<const typename Vec<V>::type *>(p);
 }
-template <int V, bool NT> __device__ __forceinline__ void vstore(float *p, const typename Vec<V>::type &x) {
-    auto *q = reinterpret_cast<typename Vec<V>::type *>(p);
-    if constexpr (NT) __builtin_nontemporal_store(x, q);
-    else *q = x;
+template <int V, bool NT, bool UA = false> __device__ __forceinline__ void vstore(float *p, const typename Vec<V>::type &x) {
+    if constexpr (UA) {
+        auto *q = reinterpret_cast<typename VecU<V>::type *>(p);
+        if constexpr (NT) __builtin_nontemporal_store(x, q);
+        else *q = x;
+    } else {
+        auto *q = reinterpret_cast<typename Vec<V>::type *>(p);
+        if constexpr (NT) __builtin_nontemporal_store(x, q);
+        else *q = x;
+    }
 }
 // Fused epilogue of a GCN-style layer: v + bias[c..c+V), then the activation (0 identity, 1 ReLU).
 // `bias_c` already points at the lane's first column, or is nullptr.

@@ -4,7 +4,9 @@
 // row next, the dense column index innermost, and only that dense column loop is tiled.  On the
 // GPU the column loop is laid across lanes: a group of G lanes covers G*V*T consecutive columns
 // (V floats per load, T loads per lane), so every read of a B row and every write of a C row is a
-// contiguous, coalesced burst.  A wavefront holds S = 64/G such groups.
+// contiguous, coalesced burst.  A wavefront holds S = 64/G such groups.  V = 4 whenever n >= 4; rows
+// that are not 16-byte aligned use the same loads at float alignment (template flag UA), and a row
+// whose length is not a multiple of 4 ends with a vector that overlaps its neighbour.
 //
 // Three paths share one launch; the workgroup index selects the path:
 //   items   one workgroup per piece of a long row; 4 wavefronts split the piece, partial sums are
@@ -22,12 +24,12 @@
 namespace scorch {
 
 // One lane group accumulates the staged entries e0, e0+es, ... (< e_end) of a row:
-//   acc[t] += val[e] * B[col[e], c0 + t*G*V .. +V)
+//   acc[t] += val[e] * B[col[e], boff[t] .. +V)
 // U gathers are issued before the first multiply so that U B-row reads are in flight per group.
-template <int V, int GV, int T, int U>
+template <int V, int T, int U, bool UA>
 __device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
                                            int e0, int e_end, int es, const float *Bc, int64_t ldb,
-                                           const bool (&colok)[T]) {
+                                           const bool (&colok)[T], const int (&boff)[T]) {
     using vec = typename Vec<V>::type;
     for (int e = e0; e < e_end; e += es * U) {
         vec x[U][T];
@@ -40,7 +42,7 @@ __device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], cons
             v[u] = ok ? lval[ee] : 0.f;
             const float *bp = Bc + (int64_t)c * ldb;
 #pragma unroll
-            for (int t = 0; t < T; ++t) x[u][t] = (ok && colok[t]) ? vload<V>(bp + t * GV) : vzero<V>();
+            for (int t = 0; t < T; ++t) x[u][t] = (ok && colok[t]) ? vload<V, UA>(bp + boff[t]) : vzero<V>();
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -67,11 +69,11 @@ __device__ __forceinline__ void reduce_groups(typename Vec<V>::type (&acc)[T]) {
 // apart (stride = 64 for a whole wavefront-row, 256 when 4 wavefronts share a piece).  Each chunk
 // is read with one coalesced load per array, parked in LDS, and broadcast from there to the lane
 // groups; the next chunk is fetched into registers while the current one is consumed.
-template <int V, int G, int T, int U, bool NTA>
+template <int V, int G, int T, int U, bool NTA, bool UA>
 __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], int *lcol, float *lval, int lane,
                                                int grp, int pfirst, int p1, int stride, const int32_t *colidx,
                                                const float *vals, const float *Bc, int64_t ldb,
-                                               const bool (&colok)[T]) {
+                                               const bool (&colok)[T], const int (&boff)[T]) {
     constexpr int S = kWave / G;
     int pc = pfirst + lane;
     int cn = 0;
@@ -90,14 +92,14 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
         }
         wave_lds_sync();
         const int cnt = min(kWave, p1 - base);
-        gather_fma<V, G * V, T, U>(acc, lcol, lval, grp, cnt, S, Bc, ldb, colok);
+        gather_fma<V, T, U, UA>(acc, lcol, lval, grp, cnt, S, Bc, ldb, colok, boff);
         wave_lds_sync();
     }
 }
 
 constexpr int smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
 
-template <int V, int G, int T, int U, int NT>
+template <int V, int G, int T, int U, int NT, bool UA>
 __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     using vec = typename Vec<V>::type;
     constexpr int S = kWave / G;
@@ -121,12 +123,20 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     uint32_t ct, b;
     if (!tile_of_workgroup(a.xcd_slices, a.ncoltiles, per_tile, ct, b)) return;
 
+    // coff[t]: first column of the lane's t-th vector.  With unaligned rows (UA) n need not be a multiple of V:
+    // the vector that would run past column n is moved back to end at n, so it overlaps its neighbour and both
+    // lanes compute and store the same values for the shared columns.
     const int c0 = (int)ct * TW + lig * V;
     bool colok[T];
+    int coff[T], boff[T];
 #pragma unroll
-    for (int t = 0; t < T; ++t) colok[t] = (c0 + t * GV) < a.n;
-    // packed B (XCD-sliced mode with a repacked copy): slice ct is a dense k x 32 block
-    const float *Bc = a.b_tile_stride ? a.B + (int64_t)ct * a.b_tile_stride + lig * V : a.B + c0;
+    for (int t = 0; t < T; ++t) {
+        colok[t] = (c0 + t * GV) < a.n;
+        coff[t] = UA ? min(c0 + t * GV, a.n - V) : c0 + t * GV;
+        // packed B (XCD-sliced mode with a repacked copy): slice ct is a dense k x 32 block
+        boff[t] = a.b_tile_stride ? lig * V + t * GV : coff[t];
+    }
+    const float *Bc = a.b_tile_stride ? a.B + (int64_t)ct * a.b_tile_stride : a.B;
 
     int *lcol = s_raw + wv * smem_ints_per_wave();
     float *lval = reinterpret_cast<float *>(lcol + kStageMax);
@@ -139,8 +149,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     if (b < (uint32_t)a.nb_items) {
         // ---- piece of a long row: 4 wavefronts, LDS tree, then C or a partial row ----
         const int4 it = a.items[b];
-        row_accumulate<V, G, T, U, NTA>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
-                                        a.vals, Bc, a.ldb, colok);
+        row_accumulate<V, G, T, U, NTA, UA>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
+                                            a.vals, Bc, a.ldb, colok, boff);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
 #pragma unroll
@@ -153,8 +163,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         }
         __syncthreads();
         if (wv == 0 && grp == 0) {
-            float *dst = it.w < 0 ? a.C + (int64_t)it.x * a.ldc + c0
-                                  : a.partials + (int64_t)it.w * a.partial_stride + c0;
+            float *dst = it.w < 0 ? a.C + (int64_t)it.x * a.ldc : a.partials + (int64_t)it.w * a.partial_stride;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 if (!colok[t]) continue;
@@ -169,8 +178,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
                     else r[i] = s;
                 }
                 // a partial row gets its epilogue in the fix-up, after the pieces are added
-                if (it.w < 0) r = apply_epilogue<V>(r, a.bias ? a.bias + c0 + t * GV : nullptr, a.act);
-                vstore<V, NTC>(dst + t * GV, r);
+                if (it.w < 0) r = apply_epilogue<V>(r, a.bias ? a.bias + coff[t] : nullptr, a.act);
+                vstore<V, NTC, UA>(dst + coff[t], r);
             }
         }
         return;
@@ -182,14 +191,14 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (idx >= a.n_wave_rows) return;
         const int row = a.wave_rows[idx];
         const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
-        row_accumulate<V, G, T, U, NTA>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, a.ldb,
-                                        colok);
+        row_accumulate<V, G, T, U, NTA, UA>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, a.ldb,
+                                            colok, boff);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
-            float *dst = a.C + (int64_t)row * a.ldc + c0;
+            float *dst = a.C + (int64_t)row * a.ldc;
 #pragma unroll
             for (int t = 0; t < T; ++t)
-                if (colok[t]) vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
+                if (colok[t]) vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(acc[t], a.bias ? a.bias + coff[t] : nullptr, a.act));
         }
         return;
     }
@@ -228,7 +237,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
             const bool ok = e < cnt;
             const int c = ok ? a.colidx[sbeg + e] : 0;
             v[i] = ok ? a.vals[sbeg + e] : 0.f;
-            x[i] = ok ? vload<V>(Bc + (int64_t)c * a.ldb) : vzero<V>();
+            x[i] = ok ? vload<V, UA>(Bc + (int64_t)c * a.ldb + boff[0]) : vzero<V>();
         }
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
@@ -242,8 +251,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         wave_lds_sync();
         if (is_short) {
             for (int q = rpv - sbeg; q < rnext - sbeg; ++q) vadd<V>(acc[0], prod[q]);
-            vstore<V, NTC>(a.C + (int64_t)(r0 + lane) * a.ldc + c0,
-                           apply_epilogue<V>(acc[0], a.bias ? a.bias + c0 : nullptr, a.act));
+            vstore<V, NTC, UA>(a.C + (int64_t)(r0 + lane) * a.ldc + coff[0],
+                           apply_epilogue<V>(acc[0], a.bias ? a.bias + coff[0] : nullptr, a.act));
         }
         return;
     }
@@ -259,11 +268,11 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (q1 - q0 > a.LW) continue;  // medium/long row: handled by another path
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-        gather_fma<V, GV, T, U>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, a.ldb, colok);
-        float *dst = a.C + (int64_t)(r0 + ri) * a.ldc + c0;
+        gather_fma<V, T, U, UA>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, a.ldb, colok, boff);
+        float *dst = a.C + (int64_t)(r0 + ri) * a.ldc;
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            if (colok[t]) vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
+            if (colok[t]) vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(acc[t], a.bias ? a.bias + coff[t] : nullptr, a.act));
     }
 }
 
@@ -272,7 +281,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
 // which shortens the serial chain of a heavy row fourfold without any scratch memory.
 constexpr int kNaturalLong = 2048;
 
-template <int V, int G, int T, int U, int NT>
+template <int V, int G, int T, int U, int NT, bool UA>
 __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) {
     using vec = typename Vec<V>::type;
     constexpr int GV = G * V;
@@ -294,8 +303,12 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     const int64_t row = row0 + wv;
     const int c0 = (int)ct * TW + lig * V;
     bool colok[T];
+    int coff[T];  // see spmm_fused_kernel
 #pragma unroll
-    for (int t = 0; t < T; ++t) colok[t] = (c0 + t * GV) < a.n;
+    for (int t = 0; t < T; ++t) {
+        colok[t] = (c0 + t * GV) < a.n;
+        coff[t] = UA ? min(c0 + t * GV, a.n - V) : c0 + t * GV;
+    }
     vec acc[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
@@ -310,15 +323,15 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     }
     __syncthreads();
     if (row < a.m && p1 - p0 <= kNaturalLong) {
-        row_accumulate<V, G, T, U, false>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, p0, p1, kWave,
-                                          a.colidx, a.vals, a.B + c0, a.ldb, colok);
+        row_accumulate<V, G, T, U, false, UA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, p0, p1, kWave,
+                                              a.colidx, a.vals, a.B, a.ldb, colok, coff);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
-            float *dst = a.C + row * a.ldc + c0;
+            float *dst = a.C + row * a.ldc;
 #pragma unroll
             for (int t = 0; t < T; ++t)
                 if (colok[t])
-                    vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(acc[t], a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
+                    vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(acc[t], a.bias ? a.bias + coff[t] : nullptr, a.act));
         }
     }
     // long rows of this workgroup, one after the other, all wavefronts on each (the loop is workgroup-uniform)
@@ -327,8 +340,8 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
         if (q1 - q0 <= kNaturalLong) continue;
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-        row_accumulate<V, G, T, U, false>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, q0 + wv * kWave, q1,
-                                          kBlock, a.colidx, a.vals, a.B + c0, a.ldb, colok);
+        row_accumulate<V, G, T, U, false, UA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, q0 + wv * kWave,
+                                              q1, kBlock, a.colidx, a.vals, a.B, a.ldb, colok, coff);
         reduce_groups<V, G, T>(acc);
         __syncthreads();  // s_red of the previous long row has been read
         if (grp == 0) {
@@ -342,7 +355,7 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
         }
         __syncthreads();
         if (wv == 0 && grp == 0) {
-            float *dst = a.C + (row0 + w) * a.ldc + c0;
+            float *dst = a.C + (row0 + w) * a.ldc;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 if (!colok[t]) continue;
@@ -356,7 +369,7 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
                     if constexpr (V == 1) r = sum;
                     else r[i] = sum;
                 }
-                vstore<V, NTC>(dst + t * GV, apply_epilogue<V>(r, a.bias ? a.bias + c0 + t * GV : nullptr, a.act));
+                vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(r, a.bias ? a.bias + coff[t] : nullptr, a.act));
             }
         }
     }
@@ -414,6 +427,7 @@ int32_t xcd_slots_for(int32_t ncoltiles);
 
 struct Mapping {
     int V, G, T, ncoltiles;
+    bool UA;  // four floats per lane at float alignment, last vector of a row moved back to end at column n
     int xcd_slices;  // 0: tile-major grid; else number of slice slots dealt over the XCDs
 };
 
@@ -421,10 +435,14 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
     Mapping mp{};
     const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(C);
     if (n % 4 == 0 && ldb % 4 == 0 && ldc % 4 == 0 && pb % 16 == 0 && pc % 16 == 0) mp.V = 4;
-    else if (n % 2 == 0 && ldb % 2 == 0 && ldc % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) mp.V = 2;
+    else if (n >= 4) {
+        // rows that are not 16-byte aligned, or n not a multiple of 4: still four floats per lane
+        mp.V = 4;
+        mp.UA = true;
+    } else if (n % 2 == 0 && ldb % 2 == 0 && ldc % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) mp.V = 2;
     else mp.V = 1;
     mp.xcd_slices = 0;
-    if (sliced && mp.V == 4) {
+    if (sliced && mp.V == 4 && !mp.UA) {
         // 32-column (one 128-byte line) slices of B, one slice per XCD at a time
         mp.G = kSliceCols / 4;
         mp.T = 1;
@@ -472,31 +490,37 @@ static int64_t grid_size(const Mapping &mp, int64_t per_tile) {
 
 typedef void (*kernel_fn)(const ExecArgs);
 
-#define SCORCH_PICK_NT(KERNEL, V, G, T, U)                                  \
-    if (NT & 1) return KERNEL<V, G, T, U, 1>;                               \
-    return KERNEL<V, G, T, U, 0>;
-#define SCORCH_PICK_U(KERNEL, V, G, T)                                      \
-    if (U >= 8) { SCORCH_PICK_NT(KERNEL, V, G, T, 8) } else { SCORCH_PICK_NT(KERNEL, V, G, T, 4) }
-#define SCORCH_PICK_G(KERNEL, V)                                            \
-    if (T == 2) { SCORCH_PICK_U(KERNEL, V, 64, 2) }                         \
+// Compiled variants: V = 4 with every group size, aligned or not; V = 2 and V = 1 only occur for n < 4, i.e. with
+// groups of 1, 2 or 4 lanes.
+#define SCORCH_PICK_NT(KERNEL, V, G, T, U, UA)                              \
+    if (NT & 1) return KERNEL<V, G, T, U, 1, UA>;                           \
+    return KERNEL<V, G, T, U, 0, UA>;
+#define SCORCH_PICK_U(KERNEL, V, G, T, UA)                                  \
+    if (U >= 8) { SCORCH_PICK_NT(KERNEL, V, G, T, 8, UA) } else { SCORCH_PICK_NT(KERNEL, V, G, T, 4, UA) }
+#define SCORCH_PICK_G4(KERNEL, UA)                                          \
+    if (T == 2) { SCORCH_PICK_U(KERNEL, 4, 64, 2, UA) }                     \
     switch (G) {                                                            \
-        case 1: SCORCH_PICK_U(KERNEL, V, 1, 1)                              \
-        case 2: SCORCH_PICK_U(KERNEL, V, 2, 1)                              \
-        case 4: SCORCH_PICK_U(KERNEL, V, 4, 1)                              \
-        case 8: SCORCH_PICK_U(KERNEL, V, 8, 1)                              \
-        case 16: SCORCH_PICK_U(KERNEL, V, 16, 1)                            \
-        case 32: SCORCH_PICK_U(KERNEL, V, 32, 1)                            \
-        default: SCORCH_PICK_U(KERNEL, V, 64, 1)                            \
+        case 1: SCORCH_PICK_U(KERNEL, 4, 1, 1, UA)                          \
+        case 2: SCORCH_PICK_U(KERNEL, 4, 2, 1, UA)                          \
+        case 4: SCORCH_PICK_U(KERNEL, 4, 4, 1, UA)                          \
+        case 8: SCORCH_PICK_U(KERNEL, 4, 8, 1, UA)                          \
+        case 16: SCORCH_PICK_U(KERNEL, 4, 16, 1, UA)                        \
+        case 32: SCORCH_PICK_U(KERNEL, 4, 32, 1, UA)                        \
+        default: SCORCH_PICK_U(KERNEL, 4, 64, 1, UA)                        \
     }
 #define SCORCH_PICK(KERNEL)                                                 \
-    switch (V) {                                                            \
-        case 4: SCORCH_PICK_G(KERNEL, 4)                                    \
-        case 2: SCORCH_PICK_G(KERNEL, 2)                                    \
-        default: SCORCH_PICK_G(KERNEL, 1)                                   \
+    if (V == 4) {                                                           \
+        if (UA) { SCORCH_PICK_G4(KERNEL, true) } else { SCORCH_PICK_G4(KERNEL, false) } \
+    }                                                                       \
+    if (V == 2) { SCORCH_PICK_U(KERNEL, 2, 1, 1, false) }                   \
+    switch (G) {                                                            \
+        case 1: SCORCH_PICK_U(KERNEL, 1, 1, 1, false)                       \
+        case 2: SCORCH_PICK_U(KERNEL, 1, 2, 1, false)                       \
+        default: SCORCH_PICK_U(KERNEL, 1, 4, 1, false)                      \
     }
 
-static kernel_fn pick_fused(int V, int G, int T, int U, int NT) { SCORCH_PICK(spmm_fused_kernel) }
-static kernel_fn pick_natural(int V, int G, int T, int U, int NT) {
+static kernel_fn pick_fused(int V, int G, int T, int U, int NT, bool UA) { SCORCH_PICK(spmm_fused_kernel) }
+static kernel_fn pick_natural(int V, int G, int T, int U, int NT, bool UA) {
     U = 8;  // the plan-free path is compiled for one unroll depth and streaming stores only
     NT = 1;
     SCORCH_PICK(spmm_natural_kernel)
@@ -552,7 +576,7 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
         a.b_tile_stride = (int64_t)plan->k * kSliceCols;
     }
     if (grid > 0) {
-        kernel_fn fn = pick_fused(mp.V, mp.G, mp.T, plan->params.U, plan->params.NT);
+        kernel_fn fn = pick_fused(mp.V, mp.G, mp.T, plan->params.U, plan->params.NT, mp.UA);
         hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "launch spmm_fused_kernel");
@@ -596,7 +620,7 @@ scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, cons
         set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);
         return SCORCH_ERR_UNSUPPORTED;
     }
-    kernel_fn fn = pick_natural(mp.V, mp.G, mp.T, U, NT);
+    kernel_fn fn = pick_natural(mp.V, mp.G, mp.T, U, NT, mp.UA);
     hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "launch spmm_natural_kernel");

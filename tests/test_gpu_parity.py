@@ -71,7 +71,7 @@ def test_leading_dimensions_and_padding(n, ldb, ldc):
     run_both(integer_valued(p, seed=4), ldc=ldc, exact=True, label=f"n={n} ldb={ldb} ldc={ldc} int")
 
 
-def test_unaligned_base_pointers_fall_back_to_narrow_loads():
+def test_base_pointers_at_float_alignment_only():
     p = csr_from_row_lengths(np.random.default_rng(1).integers(0, 50, size=200), 300, 64, seed=5)
     d = DeviceProblem(p)
     # shift B and C by one float: 4-byte aligned only
