@@ -168,8 +168,7 @@ scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spm
  * D has the sparsity pattern of A, so only its values are produced: out_vals[p] for the p-th stored
  * entry (row i, column colidx[p]).  B is m x d (row stride ldb >= d).  The second factor is passed
  * TRANSPOSED: Ct = C^T is k x d (row stride ldct >= d), so that column j of C is the contiguous row j
- * of Ct.  d must not exceed 1024 (256 when B or Ct is only 4-byte aligned, 512 for 8-byte alignment);
- * larger d gives SCORCH_ERR_UNSUPPORTED.  out_vals (float[nnz], device) may be the same array as vals
+ * of Ct.  d must not exceed 1024 (any alignment of B and Ct); larger d gives SCORCH_ERR_UNSUPPORTED.  out_vals (float[nnz], device) may be the same array as vals
  * (in place) and must otherwise not overlap any input.  fp32 products, fp32 accumulation, fixed
  * summation order.  The planned variant reuses a plan made by scorch_spmm_plan for the same rowptr
  * (any n); the plan-free variant runs one wavefront per row.

@@ -9,7 +9,10 @@
 // lane), a wavefront holds S = 64/G groups.  Eight entries are processed per group and step; their eight
 // per-lane partial dot products are reduced with a halving butterfly (4 + 2 + 1 exchanges over lane distances
 // 1, 2, 4 -- DPP and ds_swizzle -- then one exchange per remaining distance), i.e. about one cross-lane
-// operation per entry instead of log2(G).
+// operation per entry instead of log2(G).  Rows of B and Ct that are not 16-byte aligned, or d not a multiple
+// of 4, use four-float loads at float alignment (template flag UA); the vector that would run past column d is
+// moved back to end at d and the elements it shares with its neighbour are zeroed in both operands, so every
+// column enters the dot product once.
 #include "device_util.h"
 #include "spmm_internal.h"
 
@@ -60,14 +63,23 @@ template <int G> __device__ __forceinline__ float group_reduce8(float (&r)[kSddm
     return s;
 }
 
+// Zeroes the first nm (0..V-1) elements of a vector.
+template <int V> __device__ __forceinline__ void zero_head(typename Vec<V>::type &v, int nm) {
+    if constexpr (V > 1) {
+#pragma unroll
+        for (int i = 0; i < V - 1; ++i)
+            if (i < nm) v[i] = 0.f;
+    }
+}
+
 // One lane group computes the staged entries e0, e0+es, ... (< e_end) of a row whose B row is in x:
 //   out_base[e] = val[e] * <x, Ct[col[e], :]>
-template <int V, int G, int T>
+template <int V, int G, int T, bool UA>
 __device__ __forceinline__ void sddmm_entries(const typename Vec<V>::type (&x)[T], const int *lcol, const float *lval,
                                               int e0, int e_end, int es, const float *Yc, int64_t ldct,
-                                              const bool (&colok)[T], int lig, float *out_base) {
+                                              const bool (&colok)[T], const int (&coff)[T], const int (&nmask)[T],
+                                              int lig, float *out_base) {
     using vec = typename Vec<V>::type;
-    constexpr int GV = G * V;
     const int my_u = ((lig & 1) << 2) | (lig & 2) | ((lig & 4) >> 2);
     for (int e = e0; e < e_end; e += es * kSddmmBatch) {
         vec y[kSddmmBatch][T];
@@ -78,7 +90,10 @@ __device__ __forceinline__ void sddmm_entries(const typename Vec<V>::type (&x)[T
             const int c = lcol[ok ? ee : e0];
             const float *yp = Yc + (int64_t)c * ldct;
 #pragma unroll
-            for (int t = 0; t < T; ++t) y[u][t] = (ok && colok[t]) ? vload<V>(yp + t * GV) : vzero<V>();
+            for (int t = 0; t < T; ++t) {
+                y[u][t] = (ok && colok[t]) ? vload<V, UA>(yp + coff[t]) : vzero<V>();
+                if constexpr (UA) zero_head<V>(y[u][t], nmask[t]);
+            }
         }
         float r[kSddmmBatch];
 #pragma unroll
@@ -100,10 +115,10 @@ __device__ __forceinline__ void sddmm_entries(const typename Vec<V>::type (&x)[T
 }
 
 // A wavefront walks the entries [pfirst, p1) of one row in chunks of 64 that are `stride` apart.
-template <int V, int G, int T, bool NTA>
+template <int V, int G, int T, bool NTA, bool UA>
 __device__ __forceinline__ void sddmm_row(const typename Vec<V>::type (&x)[T], int *lcol, float *lval, int lane, int grp,
                                           int lig, int pfirst, int p1, int stride, const SddmmArgs &a, const float *Yc,
-                                          const bool (&colok)[T]) {
+                                          const bool (&colok)[T], const int (&coff)[T], const int (&nmask)[T]) {
     constexpr int S = kWave / G;
     int pc = pfirst + lane;
     int cn = 0;
@@ -122,20 +137,24 @@ __device__ __forceinline__ void sddmm_row(const typename Vec<V>::type (&x)[T], i
         }
         wave_lds_sync();
         const int cnt = min(kWave, p1 - base);
-        sddmm_entries<V, G, T>(x, lcol, lval, grp, cnt, S, Yc, a.ldct, colok, lig, a.out + base);
+        sddmm_entries<V, G, T, UA>(x, lcol, lval, grp, cnt, S, Yc, a.ldct, colok, coff, nmask, lig, a.out + base);
         wave_lds_sync();
     }
 }
 
-template <int V, int T>
-__device__ __forceinline__ void load_x(typename Vec<V>::type (&x)[T], const float *Bc, int GV, const bool (&colok)[T]) {
+template <int V, int T, bool UA>
+__device__ __forceinline__ void load_x(typename Vec<V>::type (&x)[T], const float *Brow, const bool (&colok)[T],
+                                       const int (&coff)[T], const int (&nmask)[T]) {
 #pragma unroll
-    for (int t = 0; t < T; ++t) x[t] = colok[t] ? vload<V>(Bc + t * GV) : vzero<V>();
+    for (int t = 0; t < T; ++t) {
+        x[t] = colok[t] ? vload<V, UA>(Brow + coff[t]) : vzero<V>();
+        if constexpr (UA) zero_head<V>(x[t], nmask[t]);
+    }
 }
 
 constexpr int sddmm_smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
 
-template <int V, int G, int T, bool PLANNED>
+template <int V, int G, int T, bool PLANNED, bool UA>
 __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
     using vec = typename Vec<V>::type;
     constexpr int S = kWave / G;
@@ -148,9 +167,14 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
     const int lig = lane % G;
     const int c0 = lig * V;
     bool colok[T];
+    int coff[T], nmask[T];  // first column of the lane's t-th vector; leading elements shared with the neighbour
 #pragma unroll
-    for (int t = 0; t < T; ++t) colok[t] = (c0 + t * GV) < a.d;
-    const float *Yc = a.Ct + c0;
+    for (int t = 0; t < T; ++t) {
+        colok[t] = (c0 + t * GV) < a.d;
+        coff[t] = UA ? min(c0 + t * GV, a.d - V) : c0 + t * GV;
+        nmask[t] = c0 + t * GV - coff[t];
+    }
+    const float *Yc = a.Ct;
     int *lcol = s_raw + wv * sddmm_smem_ints_per_wave();
     float *lval = reinterpret_cast<float *>(lcol + kStageMax);
     int *lrp = lcol + 2 * kStageMax;
@@ -161,24 +185,27 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
         // plan-free: one wavefront per row in natural order
         const int64_t row = (int64_t)b * kWavesPerBlock + wv;
         if (row >= a.m) return;
-        load_x<V, T>(x, a.B + row * a.ldb + c0, GV, colok);
-        sddmm_row<V, G, T, false>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok);
+        load_x<V, T, UA>(x, a.B + row * a.ldb, colok, coff, nmask);
+        sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok,
+                                      coff, nmask);
         return;
     }
 
     if (b < (uint32_t)a.nb_items) {
         // piece of a long row: the 4 wavefronts take interleaved chunks; entries are independent
         const int4 it = a.items[b];
-        load_x<V, T>(x, a.B + (int64_t)it.x * a.ldb + c0, GV, colok);
-        sddmm_row<V, G, T, false>(x, lcol, lval, lane, grp, lig, it.y + wv * kWave, it.z, kBlock, a, Yc, colok);
+        load_x<V, T, UA>(x, a.B + (int64_t)it.x * a.ldb, colok, coff, nmask);
+        sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, it.y + wv * kWave, it.z, kBlock, a, Yc, colok, coff,
+                                      nmask);
         return;
     }
     if (b < (uint32_t)(a.nb_items + a.nb_wave)) {
         const int idx = (int)(b - a.nb_items) * kWavesPerBlock + wv;
         if (idx >= a.n_wave_rows) return;
         const int row = a.wave_rows[idx];
-        load_x<V, T>(x, a.B + (int64_t)row * a.ldb + c0, GV, colok);
-        sddmm_row<V, G, T, false>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok);
+        load_x<V, T, UA>(x, a.B + (int64_t)row * a.ldb, colok, coff, nmask);
+        sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok,
+                                      coff, nmask);
         return;
     }
     // window of consecutive short rows: stage the window's entries once, one lane group per row
@@ -210,39 +237,44 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
     for (int ri = grp; ri < nr; ri += S) {
         const int q0 = lrp[ri], q1 = lrp[ri + 1];
         if (q1 - q0 > a.LW || q1 == q0) continue;
-        load_x<V, T>(x, a.B + (int64_t)(r0 + ri) * a.ldb + c0, GV, colok);
-        sddmm_entries<V, G, T>(x, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Yc, a.ldct, colok, lig, a.out + sbeg);
+        load_x<V, T, UA>(x, a.B + (int64_t)(r0 + ri) * a.ldb, colok, coff, nmask);
+        sddmm_entries<V, G, T, UA>(x, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Yc, a.ldct, colok, coff, nmask, lig, a.out + sbeg);
     }
 }
 
 // ------------------------------------------------------------------------------------------
 typedef void (*sddmm_fn)(const SddmmArgs);
 
-template <bool PLANNED> static sddmm_fn pick_sddmm(int V, int G, int T) {
-#define SCORCH_SD(Vv, Gg, Tt) return sddmm_kernel<Vv, Gg, Tt, PLANNED>;
-#define SCORCH_SD_G(Vv)                                   \
-    if (T == 4) { SCORCH_SD(Vv, 64, 4) }                  \
-    if (T == 2) { SCORCH_SD(Vv, 64, 2) }                  \
+// Compiled variants: V = 4 with every group size, aligned or not; V = 2 and V = 1 only occur for d < 4 (G = 8).
+template <bool PLANNED> static sddmm_fn pick_sddmm(int V, int G, int T, bool UA) {
+#define SCORCH_SD(Vv, Gg, Tt, Uu) return sddmm_kernel<Vv, Gg, Tt, PLANNED, Uu>;
+#define SCORCH_SD_G4(Uu)                                  \
+    if (T == 4) { SCORCH_SD(4, 64, 4, Uu) }               \
+    if (T == 2) { SCORCH_SD(4, 64, 2, Uu) }               \
     switch (G) {                                          \
-        case 8: SCORCH_SD(Vv, 8, 1)                       \
-        case 16: SCORCH_SD(Vv, 16, 1)                     \
-        case 32: SCORCH_SD(Vv, 32, 1)                     \
-        default: SCORCH_SD(Vv, 64, 1)                     \
+        case 8: SCORCH_SD(4, 8, 1, Uu)                    \
+        case 16: SCORCH_SD(4, 16, 1, Uu)                  \
+        case 32: SCORCH_SD(4, 32, 1, Uu)                  \
+        default: SCORCH_SD(4, 64, 1, Uu)                  \
     }
-    switch (V) {
-        case 4: SCORCH_SD_G(4)
-        case 2: SCORCH_SD_G(2)
-        default: SCORCH_SD_G(1)
+    if (V == 4) {
+        if (UA) { SCORCH_SD_G4(true) } else { SCORCH_SD_G4(false) }
     }
-#undef SCORCH_SD_G
+    if (V == 2) { SCORCH_SD(2, 8, 1, false) }
+    SCORCH_SD(1, 8, 1, false)
+#undef SCORCH_SD_G4
 #undef SCORCH_SD
 }
 
 static bool pick_sddmm_mapping(int32_t d, const float *B, int64_t ldb, const float *Ct, int64_t ldct, int &V, int &G,
-                               int &T) {
+                               int &T, bool &UA) {
     const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(Ct);
+    UA = false;
     if (d % 4 == 0 && ldb % 4 == 0 && ldct % 4 == 0 && pb % 16 == 0 && pc % 16 == 0) V = 4;
-    else if (d % 2 == 0 && ldb % 2 == 0 && ldct % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) V = 2;
+    else if (d >= 4) {
+        V = 4;
+        UA = true;
+    } else if (d % 2 == 0 && ldb % 2 == 0 && ldct % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) V = 2;
     else V = 1;
     const int lanes = (d + V - 1) / V;
     T = 1;
@@ -261,8 +293,9 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
                              const int32_t *colidx, const float *vals, const float *B, int64_t ldb, const float *Ct,
                              int64_t ldct, float *out, hipStream_t stream) {
     int V, G, T;
-    if (!pick_sddmm_mapping(d, B, ldb, Ct, ldct, V, G, T)) {
-        set_error("sddmm: d = %d exceeds the %d columns one wavefront covers with this alignment", d, 4 * kWave * V);
+    bool UA;
+    if (!pick_sddmm_mapping(d, B, ldb, Ct, ldct, V, G, T, UA)) {
+        set_error("sddmm: d = %d exceeds the %d columns one wavefront covers", d, 4 * kWave * V);
         return SCORCH_ERR_UNSUPPORTED;
     }
     SddmmArgs a{};
@@ -291,10 +324,10 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
         a.nb_win = plan->n_short > 0 ? (int32_t)((plan->layout.n_windows + kWavesPerBlock - 1) / kWavesPerBlock) : 0;
         a.LW = plan->params.LW;
         grid = (int64_t)a.nb_items + a.nb_wave + a.nb_win;
-        fn = pick_sddmm<true>(V, G, T);
+        fn = pick_sddmm<true>(V, G, T, UA);
     } else {
         grid = ((int64_t)m + kWavesPerBlock - 1) / kWavesPerBlock;
-        fn = pick_sddmm<false>(V, G, T);
+        fn = pick_sddmm<false>(V, G, T, UA);
     }
     if (grid > 0x7fffffffLL) {
         set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);

@@ -73,7 +73,7 @@ def test_sddmm_small_workloads(cfg, scale, tune):
         run_and_check(p, d, 3, planned=False, label=f"{p.name} plan-free d={d}")
 
 
-@pytest.mark.parametrize("d", [1, 2, 3, 4, 7, 8, 31, 32, 33, 64, 100, 128, 130, 255, 256, 260, 512, 516, 1000, 1024])
+@pytest.mark.parametrize("d", [1, 2, 3, 4, 5, 7, 8, 31, 32, 33, 64, 100, 128, 130, 255, 256, 257, 260, 301, 512, 516, 1000, 1001, 1023, 1024])
 def test_sddmm_inner_dimensions(d):
     rng = np.random.default_rng(d)
     lens = np.concatenate([rng.integers(0, 40, size=150), [700, 0, 300, 65, 64, 33, 32, 1, 9, 8, 7]])
@@ -84,7 +84,8 @@ def test_sddmm_inner_dimensions(d):
         run_and_check(integer_valued(p, seed=d), d, d + 2, integer=True, planned=False, label=f"d={d} int plan-free")
 
 
-@pytest.mark.parametrize("d,ldb,ldct", [(64, 72, 68), (100, 101, 103), (7, 9, 8), (128, 132, 136), (256, 260, 256)])
+@pytest.mark.parametrize("d,ldb,ldct", [(64, 72, 68), (100, 101, 103), (7, 9, 8), (128, 132, 136), (256, 260, 256), (300, 301, 303),
+                                        (1021, 1024, 1022)])
 def test_sddmm_leading_dimensions(d, ldb, ldct):
     p = csr_from_row_lengths(np.random.default_rng(3).integers(0, 90, size=300), 400, 4, seed=3)
     run_and_check(p, d, 5, ldb=ldb, ldct=ldct, label=f"d={d} ldb={ldb} ldct={ldct}")  # padding holds NaN
