@@ -14,10 +14,12 @@ from gpu_util import DeviceProblem, check_against_oracle
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("cfg,scale,tune_sliced", [(1, 1.0, False), (3, 0.08, False), (5, 0.06, True)])
-def test_planned_spmm_and_sddmm_replay_in_a_graph(cfg, scale, tune_sliced, monkeypatch):
-    if tune_sliced:
-        monkeypatch.setenv("SCORCH_SPMM_TUNE", "sliced=1,pack=1,ch=64,bch=128")  # pack pre-pass + fix-up launch in the graph
+@pytest.mark.parametrize("cfg,scale,tune", [(1, 1.0, None), (3, 0.08, None),
+                                            (5, 0.06, "sliced=1,pack=1,ch=64,bch=128"),  # pack pre-pass + fix-up launch in the graph
+                                            (5, 0.06, "panel=1"), (5, 0.06, "panel=2")])  # copy of B + panel kernel in the graph
+def test_planned_spmm_and_sddmm_replay_in_a_graph(cfg, scale, tune, monkeypatch):
+    if tune:
+        monkeypatch.setenv("SCORCH_SPMM_TUNE", tune)
     p = make_scaled_config(cfg, scale, seed=4)
     d = DeviceProblem(p)
     plan = d.make_plan()
