@@ -257,7 +257,8 @@ def main():
                     "plan": {"BN": info.BN, "ALPHA": info.ALPHA, "LW": info.LW, "CH": info.CH, "BCH": info.BCH,
                              "windows": info.n_windows, "short_rows": info.n_short_rows, "wave_rows": info.n_wave_rows,
                              "items": info.n_items, "split_rows": info.n_split_rows,
-                             "mode": {0: "gather", 1: "xcd_sliced_gather", 2: "lds_panel"}[info.mode]}})
+                             "mode": {0: "gather", 1: "xcd_sliced_gather", 2: "lds_panel"}[info.mode],
+                             "hot_columns": info.n_hot_columns, "hot_share": round(float(info.hot_share), 4)}})
         out["mode"] = out["plan"]["mode"]
         tr_ = traffic.get(CONFIG_NAMES[cfg])
         if tr_:

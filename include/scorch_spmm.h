@@ -91,7 +91,11 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * kernels are used).  The
  * call enqueues on `stream` and WAITS for it (it reads nnz and the list sizes back).  The plan is valid for exactly this rowptr content
  * and this n, on the device that was current.
- * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=.."
+ * When B is larger than the 256 MB memory-side cache and colidx is given, the plan also counts how often
+ * each column occurs and marks the most referenced columns (up to 64 MB of rows of B) as hot; execution then
+ * reads only those rows of B with the default cache policy and the others with the streaming policy.
+ * This changes no result bit.
+ * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>"
  * overrides the built-in parameter choice (for experiments).
  */
 scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
@@ -156,6 +160,8 @@ typedef struct scorch_spmm_plan_info {
     int32_t mode; /* 0 gather kernel, 1 gather kernel with XCD-sliced columns, 2 panel kernel */
     uint64_t off_win_row_start, off_wave_rows, off_items, off_split, off_partials;
     uint64_t workspace_bytes_used;
+    int32_t n_hot_columns; /* columns whose rows of B keep the default cache policy (0: no hot/cold split) */
+    float hot_share;       /* share of the stored entries that point at those columns */
 } scorch_spmm_plan_info_t;
 
 scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spmm_plan_info_t *out);

@@ -284,6 +284,8 @@ scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spm
     out->off_split = plan->layout.off_split;
     out->off_partials = plan->layout.off_partials;
     out->workspace_bytes_used = plan->layout.total;
+    out->n_hot_columns = plan->n_hot;
+    out->hot_share = plan->hot_share;
     return SCORCH_OK;
 }
 

@@ -26,7 +26,7 @@ namespace scorch {
 // One lane group accumulates the staged entries e0, e0+es, ... (< e_end) of a row:
 //   acc[t] += val[e] * B[col[e], boff[t] .. +V)
 // U gathers are issued before the first multiply so that U B-row reads are in flight per group.
-template <int V, int T, int U, bool UA>
+template <int V, int T, int U, bool UA, bool HOT = false>
 __device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
                                            int e0, int e_end, int es, const float *Bc, int64_t ldb,
                                            const bool (&colok)[T], const int (&boff)[T]) {
@@ -38,11 +38,27 @@ __device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], cons
         for (int u = 0; u < U; ++u) {
             const int ee = e + u * es;
             const bool ok = ee < e_end;
-            const int c = lcol[ok ? ee : e0];
+            int c = lcol[ok ? ee : e0];
             v[u] = ok ? lval[ee] : 0.f;
+            bool hot = true;
+            if constexpr (HOT) {
+                hot = c < 0;
+                c &= 0x7fffffff;
+            }
             const float *bp = Bc + (int64_t)c * ldb;
 #pragma unroll
-            for (int t = 0; t < T; ++t) x[u][t] = (ok && colok[t]) ? vload<V, UA>(bp + boff[t]) : vzero<V>();
+            for (int t = 0; t < T; ++t) {
+                if (ok && colok[t]) {
+                    if (hot) {
+                        x[u][t] = vload<V, UA>(bp + boff[t]);
+                    } else {
+                        asm volatile("" ::: "memory");  // keeps the two loads apart (merged, the streaming policy is lost)
+                        x[u][t] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(bp + boff[t]));
+                    }
+                } else {
+                    x[u][t] = vzero<V>();
+                }
+            }
         }
 #pragma unroll
         for (int u = 0; u < U; ++u)
@@ -69,11 +85,16 @@ __device__ __forceinline__ void reduce_groups(typename Vec<V>::type (&acc)[T]) {
 // apart (stride = 64 for a whole wavefront-row, 256 when 4 wavefronts share a piece).  Each chunk
 // is read with one coalesced load per array, parked in LDS, and broadcast from there to the lane
 // groups; the next chunk is fetched into registers while the current one is consumed.
-template <int V, int G, int T, int U, bool NTA, bool UA>
+__device__ __forceinline__ int mark_hot(int c, const uint32_t *mask) {
+    return c | (int)(((mask[c >> 5] >> (c & 31)) & 1u) << 31);
+}
+
+template <int V, int G, int T, int U, bool NTA, bool UA, bool HOT = false>
 __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], int *lcol, float *lval, int lane,
                                                int grp, int pfirst, int p1, int stride, const int32_t *colidx,
                                                const float *vals, const float *Bc, int64_t ldb,
-                                               const bool (&colok)[T], const int (&boff)[T]) {
+                                               const bool (&colok)[T], const int (&boff)[T],
+                                               const uint32_t *hotmask = nullptr) {
     constexpr int S = kWave / G;
     int pc = pfirst + lane;
     int cn = 0;
@@ -81,6 +102,7 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
     if (pc < p1) {
         cn = ld_idx<NTA>(colidx + pc);
         vn = ld_val<NTA>(vals + pc);
+        if constexpr (HOT) cn = mark_hot(cn, hotmask);
     }
     for (int base = pfirst; base < p1; base += stride) {
         lcol[lane] = cn;
@@ -89,17 +111,18 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
         if (pc < p1) {
             cn = ld_idx<NTA>(colidx + pc);
             vn = ld_val<NTA>(vals + pc);
+            if constexpr (HOT) cn = mark_hot(cn, hotmask);
         }
         wave_lds_sync();
         const int cnt = min(kWave, p1 - base);
-        gather_fma<V, T, U, UA>(acc, lcol, lval, grp, cnt, S, Bc, ldb, colok, boff);
+        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, grp, cnt, S, Bc, ldb, colok, boff);
         wave_lds_sync();
     }
 }
 
 constexpr int smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
 
-template <int V, int G, int T, int U, int NT, bool UA>
+template <int V, int G, int T, int U, int NT, bool UA, bool HOT = false>
 __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     using vec = typename Vec<V>::type;
     constexpr int S = kWave / G;
@@ -149,8 +172,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     if (b < (uint32_t)a.nb_items) {
         // ---- piece of a long row: 4 wavefronts, LDS tree, then C or a partial row ----
         const int4 it = a.items[b];
-        row_accumulate<V, G, T, U, NTA, UA>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
-                                            a.vals, Bc, a.ldb, colok, boff);
+        row_accumulate<V, G, T, U, NTA, UA, HOT>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
+                                                 a.vals, Bc, a.ldb, colok, boff, a.hotmask);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
 #pragma unroll
@@ -191,8 +214,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (idx >= a.n_wave_rows) return;
         const int row = a.wave_rows[idx];
         const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
-        row_accumulate<V, G, T, U, NTA, UA>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, a.ldb,
-                                            colok, boff);
+        row_accumulate<V, G, T, U, NTA, UA, HOT>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, a.ldb,
+                                                 colok, boff, a.hotmask);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
             float *dst = a.C + (int64_t)row * a.ldc;
@@ -257,7 +280,9 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         return;
     }
     for (int e = lane; e < cnt; e += kWave) {
-        lcol[e] = ld_idx<NTA>(a.colidx + sbeg + e);
+        int c = ld_idx<NTA>(a.colidx + sbeg + e);
+        if constexpr (HOT) c = mark_hot(c, a.hotmask);
+        lcol[e] = c;
         lval[e] = ld_val<NTA>(a.vals + sbeg + e);
     }
     lrp[lane] = rpv;
@@ -268,7 +293,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (q1 - q0 > a.LW) continue;  // medium/long row: handled by another path
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-        gather_fma<V, T, U, UA>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, a.ldb, colok, boff);
+        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, a.ldb, colok, boff);
         float *dst = a.C + (int64_t)(r0 + ri) * a.ldc;
 #pragma unroll
         for (int t = 0; t < T; ++t)
@@ -520,6 +545,15 @@ typedef void (*kernel_fn)(const ExecArgs);
     }
 
 static kernel_fn pick_fused(int V, int G, int T, int U, int NT, bool UA) { SCORCH_PICK(spmm_fused_kernel) }
+static kernel_fn pick_fused_hot(int G, int T) {
+    if (T == 2) return spmm_fused_kernel<4, 64, 2, 8, 1, false, true>;
+    switch (G) {
+        case 8: return spmm_fused_kernel<4, 8, 1, 8, 1, false, true>;
+        case 16: return spmm_fused_kernel<4, 16, 1, 8, 1, false, true>;
+        case 32: return spmm_fused_kernel<4, 32, 1, 8, 1, false, true>;
+        default: return spmm_fused_kernel<4, 64, 1, 8, 1, false, true>;
+    }
+}
 static kernel_fn pick_natural(int V, int G, int T, int U, int NT, bool UA) {
     U = 8;  // the plan-free path is compiled for one unroll depth and streaming stores only
     NT = 1;
@@ -577,6 +611,12 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     }
     if (grid > 0) {
         kernel_fn fn = pick_fused(mp.V, mp.G, mp.T, plan->params.U, plan->params.NT, mp.UA);
+        if (plan->n_hot > 0 && mp.V == 4 && !mp.UA && mp.xcd_slices == 0 && mp.G >= 8 && plan->params.U >= 8 &&
+            (plan->params.NT & 1)) {
+            // hot/cold variant: rows of B outside the plan's hot set are read with the streaming policy
+            a.hotmask = reinterpret_cast<const uint32_t *>(ws + plan->layout.off_hotmask);
+            fn = pick_fused_hot(mp.G, mp.T);
+        }
         hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "launch spmm_fused_kernel");

@@ -22,6 +22,8 @@ constexpr int kPanelCols = 256; // panel kernel: one wavefront covers 256 column
 constexpr int kPanelRows = 64;  // panel kernel: B rows per LDS panel (64 x 1 KB = 64 KB)
 constexpr int kSliceCols = 32;  // XCD-sliced mode: 32 fp32 columns = one 128-byte line of a B row
 constexpr int64_t kL2SliceBudget = 2560 * 1024;  // bytes of B an XCD's 4 MB L2 is trusted to keep resident
+constexpr int64_t kMallBytes = 256ll << 20;      // memory-side cache shared by all XCDs
+constexpr int kDegBins = 32 * 16 + 1;            // column-degree histogram: 16 bins per power of two
 
 // Parameters that decide how rows are classed and cut (paper has none of this; see the header).
 struct PlanParams {
@@ -35,16 +37,18 @@ struct PlanParams {
     int32_t SLICED; // 1: the workload suits XCD-sliced execution (see want_sliced)
     int32_t PACK;   // 1: sliced execution gathers from a slice-major copy of B made at every call
     int32_t PANEL;  // 1: dense-ish sorted rows: stream B through LDS in k-panels (spmm_panel.hip)
+    int32_t HOT;    // >0: budget in KB for the most referenced rows of B, which alone keep the default cache policy
 };
 
 struct Tuning {
-    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1, panel = -1;
+    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1, panel = -1, hot = -1;
 };
 Tuning read_tuning_from_env();
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t);
 
 struct WorkspaceLayout {
-    uint64_t off_counts, off_totals, off_win, off_wave, off_items, off_split, off_partials, off_bpack, total;
+    uint64_t off_counts, off_totals, off_win, off_wave, off_items, off_split, off_partials, off_bpack, off_coldeg,
+        off_hotmask, off_degbins, total;
     int64_t n_windows, nblk;
     int64_t cap_wave, cap_items, cap_split, cap_slots;
     int32_t partial_stride;
@@ -73,6 +77,7 @@ struct ExecArgs {
     int64_t b_tile_stride;  // 0: B is the caller's row-major matrix; else B is slice-major, floats per slice
     const float *bias;      // epilogue: n floats added to every row of C, or nullptr
     int32_t act;            // epilogue: 0 identity, 1 ReLU
+    const uint32_t *hotmask;  // one bit per column of A, set for the most referenced rows of B (hot/cold variants only)
 };
 
 struct PanelArgs {
@@ -143,6 +148,8 @@ struct scorch_spmm_plan_s {
     scorch::WorkspaceLayout layout;
     char *workspace;
     int32_t n_short, n_wave, n_items, n_split, n_slots;
+    int32_t n_hot;    // columns marked hot (0: every gather uses the default cache policy)
+    float hot_share;  // share of the stored entries that point at a hot column
 };
 
 namespace scorch {

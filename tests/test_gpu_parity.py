@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 SMALL = [(1, 1.0), (2, 0.12), (3, 0.08), (4, 0.006), (5, 0.06)]
 # parameter sets that force every execution path (windows, wave rows, single- and multi-piece block rows)
 TUNES = [None, "bn=64,alpha=2,lw=8,ch=32,bch=64,u=4,nt=0", "bn=256,lw=64,ch=256,bch=256,u=8,nt=3",
-         "bn=128,lw=0,ch=64,bch=128", "bn=32,alpha=1,lw=64,ch=64,bch=1000000"]
+         "bn=128,lw=0,ch=64,bch=128", "bn=32,alpha=1,lw=64,ch=64,bch=1000000", "hot=16,ch=64,bch=128", "hot=1"]
 
 
 def run_both(p, ldc=None, exact=False, label=""):
@@ -262,6 +262,45 @@ def test_repeated_runs_are_bit_identical():
     for _ in range(3):
         assert np.array_equal(first, d.run_planned(plan))
     plan.destroy()
+
+
+@pytest.mark.parametrize("budget_kb", [1, 8, 64, 100000])
+def test_hot_column_marking_changes_cache_policy_only(budget_kb):
+    """Forced hot/cold split: the set of hot columns follows the stated rule (whole degree bins from the top while they
+    fit the byte budget, 16 bins per power of two), and the result is bit-identical to the run without the split."""
+    p = make_scaled_config(3, 0.08, seed=12)  # power-law columns
+    d = DeviceProblem(p)
+    plan0 = d.make_plan()
+    base = d.run_planned(plan0).copy()
+    assert plan0.info().n_hot_columns == 0  # B is far smaller than the memory-side cache: no split by default
+    plan0.destroy()
+    with tuning(f"hot={budget_kb}"):
+        plan = d.make_plan()
+        info = plan.info()
+        deg = np.bincount(p.colidx, minlength=p.k)
+
+        def degree_bin(x):
+            if x <= 0:
+                return 0
+            e = int(x).bit_length() - 1
+            frac = (x >> (e - 4)) & 15 if e >= 4 else (x << (4 - e)) & 15
+            return e * 16 + frac + 1
+
+        bins = np.array([degree_bin(int(x)) for x in deg])
+        max_rows = max(1, budget_kb * 1024 // (((p.n * 4 + 127) // 128) * 128))
+        rows, entries = 0, 0
+        for b in range(bins.max(), 0, -1):
+            cnt = int((bins == b).sum())
+            if rows + cnt > max_rows:
+                break
+            rows += cnt
+            entries += int(deg[bins == b].sum())
+        assert info.n_hot_columns == rows
+        assert abs(info.hot_share - entries / p.nnz) < 1e-6
+        out = d.run_planned(plan)
+        assert np.array_equal(out, base)
+        check_against_oracle(p, out, d.ldc, label=f"hot={budget_kb}")
+        plan.destroy()
 
 
 def test_runs_on_a_side_stream():
