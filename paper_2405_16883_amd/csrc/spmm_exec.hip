@@ -129,7 +129,10 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     constexpr int GV = G * V;
     constexpr int TW = GV * T;
     constexpr bool NTC = (NT & 1) != 0;  // streaming stores for C
-    constexpr bool NTA = false;          // colidx/vals are read with plain loads (a streaming hint made no difference)
+    // colidx/vals are read with plain loads (a streaming hint made no difference), except in the hot/cold variants:
+    // there the memory-side cache is reserved for the hot rows of B and the 8 bytes per entry of A would only
+    // displace them (workload 4: another 2.7 % less time)
+    constexpr bool NTA = HOT;
 
     __shared__ int s_raw[kWavesPerBlock * smem_ints_per_wave()];
     __shared__ float s_red[kWavesPerBlock * TW];
