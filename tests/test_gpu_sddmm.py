@@ -116,3 +116,33 @@ def test_sddmm_full_size_gcn_graph():
     p = make_config(3, seed=0)
     run_and_check(p, 128, 11, label="workload 3 pattern, d=128")
     run_and_check(integer_valued(p, seed=5), 128, 12, integer=True, label="workload 3 pattern int")
+
+
+@pytest.mark.parametrize("block", range(6))
+def test_sddmm_random_small_problems(block):
+    """Seeded random shapes, row-length mixes, leading dimensions and forced plan parameters."""
+    for i in range(block * 15, block * 15 + 15):
+        rng = np.random.default_rng(5000 + i)
+        m = int(rng.choice([1, 3, 17, 64, 65, 130, 300]))
+        k = int(rng.choice([1, 2, 31, 33, 100, 700, 2500]))
+        d = int(rng.choice([1, 2, 3, 4, 5, 8, 31, 32, 33, 64, 65, 100, 127, 128, 129, 256, 257, 300, 513, 1000, 1023]))
+        kind = int(rng.integers(0, 3))
+        if kind == 0:
+            lens = rng.integers(0, min(k, 40) + 1, size=m)
+        elif kind == 1:
+            lens = np.minimum((rng.pareto(1.2, size=m) * 3).astype(np.int64), 3 * k)
+        else:
+            lens = np.zeros(m, dtype=np.int64)
+            lens[rng.integers(0, m, size=max(1, m // 8))] = int(rng.integers(1, 2000))
+        dup = bool(rng.integers(0, 2)) or int(lens.max(initial=0)) > k
+        p = csr_from_row_lengths(lens, k, 4, seed=i, duplicates=dup, sorted_cols=bool(rng.integers(0, 2)))
+        ldb = d + int(rng.choice([0, 0, 1, 3, 4]))
+        ldct = d + int(rng.choice([0, 0, 1, 2, 4]))
+        tune = TUNES[int(rng.integers(0, len(TUNES)))]
+        label = f"case {i}: m={m} k={k} d={d} nnz={p.nnz} ldb={ldb} ldct={ldct} [{tune}]"
+        print(label, flush=True)
+        with tuning(tune):
+            run_and_check(p, d, i, ldb=ldb, ldct=ldct, label=label)
+            run_and_check(integer_valued(p, seed=i), d, i + 1, integer=True, ldb=ldb, ldct=ldct, label=label + " int")
+            run_and_check(integer_valued(p, seed=i), d, i + 2, integer=True, ldb=ldb, ldct=ldct, planned=False,
+                          label=label + " int plan-free")
