@@ -388,8 +388,9 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     p.ALPHA = 4;
     // Windows of 128 key units, but small problems get smaller windows so that there are a few thousand
     // wavefronts' worth of them (a lane group walks its rows one after the other, each a full memory latency).
-    // For n <= 4 the lanes of a wavefront split a window's entries, so larger windows keep more lanes busy.
-    const int32_t bn_cap = n <= 4 ? kBNMax : 128;
+    // Narrow B (n <= 32) means 8 or more lane groups per wavefront, each walking one row of the window (for n <= 4
+    // the lanes split the window's entries): larger windows keep more of them busy.
+    const int32_t bn_cap = n <= 32 ? kBNMax : 128;
     p.BN = std::min<int32_t>(bn_cap, std::max<int32_t>(16, pow2_floor(std::max<int64_t>(1, (nnz + (int64_t)p.ALPHA * m) / 4096))));
     p.LW = 32;
     p.SLICED = want_sliced(m, k, nnz, n) ? 1 : 0;
