@@ -14,7 +14,7 @@
 //
 //   workgroup = 16 wavefronts = 64 rows x one tile of C (256 or 512 columns), one workgroup per CU
 //   wavefront = 4 rows, lane l owns columns 4l..4l+3 (and 256+4l.. for the wide tile), accumulators in registers
-//   panel     = 64 KB of a tile-major copy of B (64 rows x 256 columns or 32 rows x 512 columns), two in LDS
+//   panel     = 64 rows x 256 columns (64 KB) or 40 rows x 512 columns (80 KB) of a tile-major copy of B, two in LDS
 // Column tiles are dealt to the XCDs (tile_of_workgroup) so that the workgroups that walk the same
 // tile of B run on the same die, start together and find the panels in that die's L2.
 #include "spmm_internal.h"
@@ -26,7 +26,8 @@ namespace scorch {
 typedef float f4 __attribute__((ext_vector_type(4)));
 
 // Template parameters: RW rows per wavefront, kBatch entries whose LDS reads are in flight together, Q float4 per
-// lane (the tile is 256*Q columns wide), KR rows of B per panel (KR * Q KB of LDS, 64 KB in both shapes used).
+// lane (the tile is 256*Q columns wide), KR rows of B per panel (KR * Q KB of LDS: 64 KB for the narrow tile, where a
+// panel may not be taller than a row's 64-entry window, 80 KB for the wide one, which fills the 160 KB of a CU).
 //
 // The panel is double-buffered: one 1024-thread workgroup per CU holds two panels in LDS.  The next panel is
 // fetched straight from global memory into LDS (global_load_lds_dwordx4: no registers, no ds_write) while the
@@ -122,6 +123,8 @@ __global__ __launch_bounds__(16 * kWave) void spmm_panel_kernel(const PanelArgs 
     constexpr int WPB = 16;
     constexpr int kRowQuads = Q * (kPanelCols / 4);
     constexpr int kRows = KR;
+    static_assert(KR <= kWave, "a panel must not take more entries of a row than its 64-entry window holds");
+    static_assert((KR * Q) % 16 == 0 && 2 * KR * Q <= 160, "two panels of KR*Q KB, dealt to 16 wavefronts, in 160 KB of LDS");
     __shared__ f4 s_b0[kRows * kRowQuads];
     __shared__ f4 s_b1[kRows * kRowQuads];
     const int tid = threadIdx.x;
@@ -193,9 +196,9 @@ bool panel_operands_ok(int32_t n, const float *B, int64_t ldb, const float *C, i
 scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowptr, const int32_t *colidx,
                              const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                              const float *bias, int32_t act, hipStream_t stream) {
-    // Two shapes: tile of 256 columns with 64-row panels, or tile of 512 columns with 32-row panels (the wide
+    // Two shapes: tile of 256 columns with 64-row panels, or tile of 512 columns with 40-row panels (the wide
     // tile halves the per-entry broadcast overhead and is chosen for denser matrices and n >= 512).  Both use
-    // 64 rows per workgroup and 128 KB of LDS, i.e. one workgroup and four wavefronts per SIMD on a CU.
+    // 64 rows per workgroup and 128 or 160 KB of LDS, i.e. one workgroup and four wavefronts per SIMD on a CU.
     const int variant = plan->params.PANEL;
     struct Shape { int RW, WPB, Q; };
     const Shape sh = variant == 2 ? Shape{4, 16, 2} : Shape{4, 16, 1};
@@ -224,7 +227,7 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
         return SCORCH_ERR_UNSUPPORTED;
     }
     const dim3 g((uint32_t)grid), b(sh.WPB * kWave);
-    if (variant == 2) hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 32>), g, b, 0, stream, a);
+    if (variant == 2) hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 40>), g, b, 0, stream, a);
     else hipLaunchKernelGGL((spmm_panel_kernel<4, 4, 1, 64>), g, b, 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "launch spmm_panel_kernel");

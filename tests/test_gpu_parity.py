@@ -134,7 +134,7 @@ def test_panel_kernel_forced(m, k, n, shape):
 
 
 @pytest.mark.parametrize("shape", [1, 2])
-@pytest.mark.parametrize("k", [1, 31, 32, 33, 64, 65, 200])
+@pytest.mark.parametrize("k", [1, 31, 32, 33, 39, 40, 41, 64, 65, 80, 81, 200])
 def test_panel_kernel_fully_dense_rows(k, shape):
     """Every row stores all k columns: each panel takes a whole 32- or 64-entry stretch of a row's register window,
     so the window is replaced at every panel; k around the panel heights covers the ragged last panel."""
