@@ -451,12 +451,11 @@ __global__ __launch_bounds__(kBlock) void spmm_fixup_kernel(const FixupArgs a) {
 // ------------------------------------------------------------------------------------------
 // host side: pick the lane mapping from n and the operand alignment, then launch
 // ------------------------------------------------------------------------------------------
-int32_t xcd_slots_for(int32_t ncoltiles);
 
 struct Mapping {
     int V, G, T, ncoltiles;
     bool UA;  // four floats per lane at float alignment, last vector of a row moved back to end at column n
-    int xcd_slices;  // 0: tile-major grid; else number of slice slots dealt over the XCDs
+    int xcd_slices;  // 0: tile-major grid; 1: column slices dealt over the XCDs (see tile_of_workgroup)
 };
 
 static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc, bool sliced) {
@@ -475,7 +474,7 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
         mp.G = kSliceCols / 4;
         mp.T = 1;
         mp.ncoltiles = (n + kSliceCols - 1) / kSliceCols;
-        mp.xcd_slices = xcd_slots_for(mp.ncoltiles);
+        mp.xcd_slices = 1;
         return mp;
     }
     const int lanes = (n + mp.V - 1) / mp.V;
@@ -499,17 +498,11 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
 // Number of workgroups for `per_tile` units of row work per column tile (see tile_of_workgroup).
 int64_t xcd_grid_size(int32_t xcd_slices, int32_t ncoltiles, int64_t per_tile) {
     if (xcd_slices == 0) return per_tile * ncoltiles;
-    if (xcd_slices >= kXcds) return (int64_t)kXcds * per_tile * ((ncoltiles + kXcds - 1) / kXcds);
-    const int64_t share = kXcds / xcd_slices;
-    return (int64_t)kXcds * ((per_tile + share - 1) / share);
-}
-
-// Slice slots dealt over the XCDs: all tiles when there are at least 8, else the next power of two.
-int32_t xcd_slots_for(int32_t ncoltiles) {
-    if (ncoltiles >= kXcds) return ncoltiles;
-    int slots = 1;
-    while (slots < ncoltiles) slots <<= 1;
-    return slots;
+    int64_t q = (int64_t)(ncoltiles / kXcds) * per_tile;
+    const int rest = ncoltiles % kXcds;
+    for (int s = kXcds / 2; s >= 1; s >>= 1)
+        if (rest & s) q += (per_tile * s + kXcds - 1) / kXcds;
+    return q * kXcds;
 }
 
 static int64_t grid_size(const Mapping &mp, int64_t per_tile) {

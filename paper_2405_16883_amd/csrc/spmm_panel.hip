@@ -218,7 +218,7 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
     a.n = plan->n;
     a.nrb = (plan->m + sh.WPB * sh.RW - 1) / (sh.WPB * sh.RW);
     a.ntiles = (plan->n + W - 1) / W;
-    a.xcd_slices = xcd_slots_for(a.ntiles);
+    a.xcd_slices = 1;
     a.bias = bias;
     a.act = act;
     const int64_t grid = xcd_grid_size(a.xcd_slices, a.ntiles, a.nrb);

@@ -360,14 +360,16 @@ static int32_t pow2_floor(int64_t x) {
     return p;
 }
 
-// XCD-sliced execution pays when B as a whole overflows an XCD's L2 but a 128-byte-wide column
-// slice of it fits, and rows are long enough that re-reading colidx/vals once per slice is cheap
-// next to the gathers (8 bytes of A against 128 bytes of B per entry and slice).
+// XCD-sliced execution pays when B as a whole overflows an XCD's 4 MB L2 at least twice over but a 128-byte-wide
+// column slice of it fits, and rows are long enough that re-reading colidx/vals and walking the row once per slice
+// is cheap next to the gathers (8 bytes of A against 128 bytes of B per entry and slice).  Measured on uniform random
+// patterns: 164 entries per row, B 8-32 MB: 1.3-2.1x faster than the plain gather; 82 entries, B 8-33 MB: 1.0-1.5x;
+// 65 entries: even; 33-41 entries: 1.2-1.4x slower; B of 4 MB (mostly L2-resident anyway): 1.1-1.3x slower.
 static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
     if (m <= 0 || n % 4 != 0 || n < 2 * kSliceCols) return false;
     const int64_t slice_bytes = (int64_t)k * kSliceCols * 4;
     const int64_t b_bytes = (int64_t)k * n * 4;
-    return slice_bytes <= kL2SliceBudget && b_bytes > kL2SliceBudget && nnz / m >= 32;
+    return slice_bytes <= kL2SliceBudget && b_bytes >= 8ll << 20 && nnz / m >= 64;
 }
 
 // The panel kernel (spmm_panel.hip) streams all of B through LDS once per block of 64 rows of A, a cost that does
