@@ -373,16 +373,20 @@ static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
 }
 
 // The panel kernel (spmm_panel.hip) streams all of B through LDS once per block of 64 rows of A, a cost that does
-// not depend on nnz, and then pays per entry about 40 % less than the gather kernels.  Measured on 4096 x 16384
-// weights with n = 2048 it wins from about 4 % stored entries upwards and loses below (2.5 %: 0.77 against 0.70 ms);
-// it needs a workgroup (64 rows x 256 or 512 columns) for every CU: with 128 blocks of 64 x 256 it loses at any
-// density, with 256 it wins by 15 %.  Returns the kernel shape (0 = do not use).
+// not depend on nnz, and then pays per entry less than the gather kernels.  It needs a workgroup (64 rows x 512 or
+// 256 columns) for every CU.  From sweeps over unstructured-pruned shapes (4096..65536 rows, k 2048..16384):
+//   wide tiles (n >= 512): ahead of the gather kernels from 3 % stored entries upwards (3 %: 0.70 against 0.73 ms,
+//     4 %: 0.39 against 0.47, 6 %: 0.48 against 0.70, 10 %: 0.65 against 1.12), behind with fewer than 256 workgroups;
+//   narrow tiles: about even with the gather kernels at 10 % (0.50 against 0.52 ms, 0.54 against 0.62), behind at
+//     4-8 %; used from 10 % upwards when only they give 256 workgroups.
+// Returns the kernel shape (0 = do not use, 1 = 256-column tiles, 2 = 512-column tiles).
 static int32_t want_panel(int32_t m, int32_t k, int64_t nnz, int32_t n) {
-    if (m <= 0 || k < 1024 || n % 4 != 0 || n < kPanelCols) return 0;
+    if (m <= 0 || k < 1024 || n % 4 != 0 || n < kPanelCols || nnz / m < 128) return 0;
     const double density = (double)nnz / ((double)m * (double)k);
-    const int64_t tasks = (int64_t)((m + 63) / 64) * ((n + kPanelCols - 1) / kPanelCols);
-    if (density < 0.04 || nnz / m < 128 || tasks < 256) return 0;
-    return (density >= 0.08 && n >= 2 * kPanelCols && tasks >= 512) ? 2 : 1;  // 2: 512-column tiles
+    const int64_t row_blocks = ((int64_t)m + 63) / 64;
+    if (n >= 2 * kPanelCols && density >= 0.03 && row_blocks * ((n + 2 * kPanelCols - 1) / (2 * kPanelCols)) >= 256) return 2;
+    if (density >= 0.1 && row_blocks * ((n + kPanelCols - 1) / kPanelCols) >= 256) return 1;
+    return 0;
 }
 
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t) {
