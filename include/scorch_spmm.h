@@ -91,7 +91,7 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * kernels are used).  The
  * call enqueues on `stream` and WAITS for it (it reads nnz and the list sizes back).  The plan is valid for exactly this rowptr content
  * and this n, on the device that was current.
- * When B is more than three times the 256 MB memory-side cache and colidx is given, the plan also counts how often
+ * When B is more than three times the 256 MB memory-side cache, n >= 96 and colidx is given, the plan also counts how often
  * each column occurs and marks the most referenced columns (up to 64 MB of rows of B) as hot; execution then
  * reads only those rows of B with the default cache policy and the others with the streaming policy.
  * This changes no result bit.

@@ -417,7 +417,8 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     // B several times larger than the memory-side cache: see build_plan (hot columns).  Budget: a quarter of that
     // cache.  Measured on the large power-law pattern: B 3.8x / 4.9x / 9.8x the cache: 5-6 % less time; 2.4x: 4 % more;
     // 1.2x: 57 % more (the cache then holds most of B anyway and the streaming policy forfeits that).
-    p.HOT = ((int64_t)k * n * 4 > 3 * kMallBytes && nnz >= 4 * (int64_t)k) ? (int32_t)(kMallBytes / 4 / 1024) : 0;
+    // Rows of B narrower than three cache lines lose with it on every pattern tried (n = 64: 4-18 % more time).
+    p.HOT = ((int64_t)k * n * 4 > 3 * kMallBytes && n >= 96 && nnz >= 4 * (int64_t)k) ? (int32_t)(kMallBytes / 4 / 1024) : 0;
     if (t.hot >= 0) p.HOT = t.hot;
     if (t.bn > 0) p.BN = t.bn;
     if (t.alpha > 0) p.ALPHA = t.alpha;
