@@ -36,14 +36,14 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 template <int Q, int KR>
 __device__ __forceinline__ void panel_fetch(const f4 *Bt, int k, int k0, f4 *sbuf, int wv, int lane) {
     constexpr int kRowQuads = Q * (kPanelCols / 4);
-    const int64_t q0 = (int64_t)k0 * kRowQuads, qend = (int64_t)k * kRowQuads;
-    // the panel is one contiguous range of the tile: KR * Q chunks of 1 KB, dealt to the 16 wavefronts; a chunk
-    // is half a row or a row of B, so it lies wholly inside or wholly outside the tile
+    // The panel is one contiguous range of the tile: KR * Q chunks of 1 KB, dealt to the 16 wavefronts; a chunk is
+    // half a row or a row of B, so it lies wholly inside or wholly outside the tile.  The wavefront-uniform parts
+    // (panel base, validity of a chunk) are kept in scalar registers; a lane adds only its 32-bit offset.
+    const f4 *panel = Bt + (int64_t)k0 * kRowQuads;
 #pragma unroll
     for (int c = 0; c < KR * Q / 16; ++c) {
         const int chunk = c * 16 + wv;
-        const int64_t g = q0 + chunk * 64;
-        if (g < qend) __builtin_amdgcn_global_load_lds(Bt + g + lane, sbuf + chunk * 64, 16, 0, 0);
+        if (k0 + chunk / Q < k) __builtin_amdgcn_global_load_lds(panel + (uint32_t)(chunk * 64 + lane), sbuf + chunk * 64, 16, 0, 0);
     }
 }
 
@@ -70,7 +70,8 @@ __device__ __forceinline__ void panel_compute(PanelRows<RW, kBatch, Q> &st, cons
     bool shift[RW];
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
-        lim[r] = __builtin_popcountll(__ballot(st.colreg[r] < kend));
+        lim[r] = (int)__builtin_popcountll(__ballot(st.colreg[r] < kend));
+        asm("" : "+s"(lim[r]));  // a 32-bit scalar from here on (else the comparisons below are done in 64 bits on the VALU)
         j[r] = st.pos[r];
         shift[r] = lim[r] > kWave - kRows && st.wbase[r] + lim[r] < st.pend[r];
         if (shift[r]) {
@@ -81,28 +82,37 @@ __device__ __forceinline__ void panel_compute(PanelRows<RW, kBatch, Q> &st, cons
     }
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
-        for (int jj = j[r]; jj < lim[r]; jj += kBatch) {
-            // issue the LDS reads of a whole batch first, then the multiply-adds; all branches are
-            // wave-uniform (scalar), entries past lim are skipped
+        // Whole batches first, without a test per entry (all branches here are wave-uniform, and the scalar
+        // instructions of such tests cost issue slots like vector ones: this loop is bound by instruction issue), then
+        // the remaining entries one at a time.  In each step the LDS reads are issued before the multiply-adds.
+        int jj = j[r];
+        for (; jj + kBatch <= lim[r]; jj += kBatch) {
             f4 x[kBatch][Q];
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                if (jj + u < lim[r]) {
-                    const int c = __builtin_amdgcn_readlane(st.colreg[r], jj + u);
+                const int c = __builtin_amdgcn_readlane(st.colreg[r], jj + u);
 #pragma unroll
-                    for (int q = 0; q < Q; ++q) x[u][q] = sbuf[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
-                }
+                for (int q = 0; q < Q; ++q) x[u][q] = sbuf[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
             }
 #pragma unroll
             for (int u = 0; u < kBatch; ++u) {
-                if (jj + u < lim[r]) {
-                    const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.valreg[r]), jj + u));
+                const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.valreg[r]), jj + u));
 #pragma unroll
-                    for (int q = 0; q < Q; ++q)
+                for (int q = 0; q < Q; ++q)
 #pragma unroll
-                        for (int i = 0; i < 4; ++i) st.acc[r][q][i] = __builtin_fmaf(v, x[u][q][i], st.acc[r][q][i]);
-                }
+                    for (int i = 0; i < 4; ++i) st.acc[r][q][i] = __builtin_fmaf(v, x[u][q][i], st.acc[r][q][i]);
             }
+        }
+        for (; jj < lim[r]; ++jj) {
+            f4 x[Q];
+            const int c = __builtin_amdgcn_readlane(st.colreg[r], jj);
+#pragma unroll
+            for (int q = 0; q < Q; ++q) x[q] = sbuf[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
+            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.valreg[r]), jj));
+#pragma unroll
+            for (int q = 0; q < Q; ++q)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) st.acc[r][q][i] = __builtin_fmaf(v, x[q][i], st.acc[r][q][i]);
         }
     }
 #pragma unroll
