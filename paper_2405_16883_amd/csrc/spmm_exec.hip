@@ -23,48 +23,75 @@
 
 namespace scorch {
 
-// One lane group accumulates the staged entries e0, e0+es, ... (< e_end) of a row:
-//   acc[t] += val[e] * B[col[e], boff[t] .. +V)
-// U gathers are issued before the first multiply so that U B-row reads are in flight per group.
-template <int V, int T, int U, bool UA, bool HOT = false>
-__device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
-                                           int e0, int e_end, int es, const float *Bc, int64_t ldb,
-                                           const bool (&colok)[T], const int (&boff)[T]) {
+// Address of row c of B as seen by one lane (base = B + the lane's column offset): one 32x32->64-bit multiply
+// and one shift-add (c >= 0 and the row stride fit 32 bits).
+__device__ __forceinline__ const float *b_row(const float *base, int c, uint32_t ldb) {
+    return base + (uint64_t)(uint32_t)c * ldb;
+}
+
+// One batch of U staged entries e, e+es, ... of a row:  acc[t] += val * B[col, boff[t] .. +V).  The U gathers
+// are issued before the first multiply so that U reads of B rows are in flight per group.  PRED: entries at or
+// past e_end are skipped (last batch of a row); otherwise the batch is whole and nothing is tested per entry.
+template <int V, int T, int U, bool UA, bool HOT, bool PRED>
+__device__ __forceinline__ void gather_batch(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
+                                             int e, int e_end, int es, const float *const (&bbase)[T],
+                                             uint32_t ldb) {
     using vec = typename Vec<V>::type;
-    for (int e = e0; e < e_end; e += es * U) {
-        vec x[U][T];
-        float v[U];
+    vec x[U][T];
+    float v[U];
+    int c[U];
 #pragma unroll
-        for (int u = 0; u < U; ++u) {
-            const int ee = e + u * es;
-            const bool ok = ee < e_end;
-            int c = lcol[ok ? ee : e0];
-            v[u] = ok ? lval[ee] : 0.f;
-            bool hot = true;
-            if constexpr (HOT) {
-                hot = c < 0;
-                c &= 0x7fffffff;
-            }
-            const float *bp = Bc + (int64_t)c * ldb;
+    for (int u = 0; u < U; ++u) {
+        const int ee = e + u * es;
+        const bool ok = !PRED || ee < e_end;
+        c[u] = lcol[ok ? ee : e];
+        v[u] = ok ? lval[ee] : 0.f;
+    }
 #pragma unroll
-            for (int t = 0; t < T; ++t) {
-                if (ok && colok[t]) {
-                    if (hot) {
-                        x[u][t] = vload<V, UA>(bp + boff[t]);
-                    } else {
-                        asm volatile("" ::: "memory");  // keeps the two loads apart (merged, the streaming policy is lost)
-                        x[u][t] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(bp + boff[t]));
-                    }
+    for (int u = 0; u < U; ++u) {
+        const bool ok = !PRED || e + u * es < e_end;
+        const bool hot = !HOT || c[u] < 0;
+        const int cu = HOT ? (c[u] & 0x7fffffff) : c[u];
+#pragma unroll
+        for (int t = 0; t < T; ++t) {
+            const float *bp = b_row(bbase[t], cu, ldb);
+            if (ok) {
+                if (hot) {
+                    x[u][t] = vload<V, UA>(bp);
                 } else {
-                    x[u][t] = vzero<V>();
+                    // the empty statements keep this load from being merged with the one of the other branch
+                    // (hoisted above or sunk below the branch, the merged load loses the streaming policy)
+                    asm volatile("");
+                    x[u][t] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(bp));
+                    asm volatile("");
                 }
+            } else {
+                x[u][t] = vzero<V>();
             }
         }
-#pragma unroll
-        for (int u = 0; u < U; ++u)
-#pragma unroll
-            for (int t = 0; t < T; ++t) vfma<V>(acc[t], v[u], x[u][t]);
     }
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+        for (int t = 0; t < T; ++t) vfma<V>(acc[t], v[u], x[u][t]);
+}
+
+// One lane group accumulates the staged entries e0, e0+es, ... (< e_end) of a row: whole batches first, then
+// one partial batch.  boff[t] is a readable offset in every lane (lanes past column n point at the last
+// vector of the row), so the loads carry no column test; `active` is false in the lanes whose first vector lies
+// past column n: they skip the row altogether.
+template <int V, int T, int U, bool UA, bool HOT = false>
+__device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
+                                           int e0, int e_end, int es, const float *Bc, uint32_t ldb, bool active,
+                                           const int (&boff)[T]) {
+    if (!active) return;
+    const float *bbase[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) bbase[t] = Bc + boff[t];
+    int e = e0;
+    for (; e + (U - 1) * es < e_end; e += U * es)
+        gather_batch<V, T, U, UA, HOT, false>(acc, lcol, lval, e, e_end, es, bbase, ldb);
+    if (e < e_end) gather_batch<V, T, U, UA, HOT, true>(acc, lcol, lval, e, e_end, es, bbase, ldb);
 }
 
 // Adds up the S = 64/G lane groups of a wavefront (xor butterfly over the lane distances G..32; DPP,
@@ -92,8 +119,8 @@ __device__ __forceinline__ int mark_hot(int c, const uint32_t *mask) {
 template <int V, int G, int T, int U, bool NTA, bool UA, bool HOT = false>
 __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], int *lcol, float *lval, int lane,
                                                int grp, int pfirst, int p1, int stride, const int32_t *colidx,
-                                               const float *vals, const float *Bc, int64_t ldb,
-                                               const bool (&colok)[T], const int (&boff)[T],
+                                               const float *vals, const float *Bc, uint32_t ldb,
+                                               bool active, const int (&boff)[T],
                                                const uint32_t *hotmask = nullptr) {
     constexpr int S = kWave / G;
     int pc = pfirst + lane;
@@ -115,7 +142,7 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
         }
         wave_lds_sync();
         const int cnt = min(kWave, p1 - base);
-        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, grp, cnt, S, Bc, ldb, colok, boff);
+        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, grp, cnt, S, Bc, ldb, active, boff);
         wave_lds_sync();
     }
 }
@@ -151,18 +178,20 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
 
     // coff[t]: first column of the lane's t-th vector.  With unaligned rows (UA) n need not be a multiple of V:
     // the vector that would run past column n is moved back to end at n, so it overlaps its neighbour and both
-    // lanes compute and store the same values for the shared columns.
+    // lanes compute and store the same values for the shared columns.  Vectors wholly past column n (colok false)
+    // point at the last vector of the row as well: they may be read, and are never stored.
     const int c0 = (int)ct * TW + lig * V;
     bool colok[T];
     int coff[T], boff[T];
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         colok[t] = (c0 + t * GV) < a.n;
-        coff[t] = UA ? min(c0 + t * GV, a.n - V) : c0 + t * GV;
+        coff[t] = min(c0 + t * GV, a.n - V);
         // packed B (XCD-sliced mode with a repacked copy): slice ct is a dense k x 32 block
         boff[t] = a.b_tile_stride ? lig * V + t * GV : coff[t];
     }
     const float *Bc = a.b_tile_stride ? a.B + (int64_t)ct * a.b_tile_stride : a.B;
+    const uint32_t ldb = (uint32_t)a.ldb;
 
     int *lcol = s_raw + wv * smem_ints_per_wave();
     float *lval = reinterpret_cast<float *>(lcol + kStageMax);
@@ -176,7 +205,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         // ---- piece of a long row: 4 wavefronts, LDS tree, then C or a partial row ----
         const int4 it = a.items[b];
         row_accumulate<V, G, T, U, NTA, UA, HOT>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
-                                                 a.vals, Bc, a.ldb, colok, boff, a.hotmask);
+                                                 a.vals, Bc, ldb, colok[0], boff, a.hotmask);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
 #pragma unroll
@@ -217,8 +246,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (idx >= a.n_wave_rows) return;
         const int row = a.wave_rows[idx];
         const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
-        row_accumulate<V, G, T, U, NTA, UA, HOT>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, a.ldb,
-                                                 colok, boff, a.hotmask);
+        row_accumulate<V, G, T, U, NTA, UA, HOT>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, ldb,
+                                                 colok[0], boff, a.hotmask);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
             float *dst = a.C + (int64_t)row * a.ldc;
@@ -263,7 +292,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
             const bool ok = e < cnt;
             const int c = ok ? a.colidx[sbeg + e] : 0;
             v[i] = ok ? a.vals[sbeg + e] : 0.f;
-            x[i] = ok ? vload<V, UA>(Bc + (int64_t)c * a.ldb + boff[0]) : vzero<V>();
+            x[i] = ok ? vload<V, UA>(b_row(Bc, c, ldb) + boff[0]) : vzero<V>();
         }
 #pragma unroll
         for (int i = 0; i < kSteps; ++i) {
@@ -296,7 +325,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (q1 - q0 > a.LW) continue;  // medium/long row: handled by another path
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, a.ldb, colok, boff);
+        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, ldb, colok[0], boff);
         float *dst = a.C + (int64_t)(r0 + ri) * a.ldc;
 #pragma unroll
         for (int t = 0; t < T; ++t)
@@ -335,7 +364,7 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
 #pragma unroll
     for (int t = 0; t < T; ++t) {
         colok[t] = (c0 + t * GV) < a.n;
-        coff[t] = UA ? min(c0 + t * GV, a.n - V) : c0 + t * GV;
+        coff[t] = min(c0 + t * GV, a.n - V);
     }
     vec acc[T];
 #pragma unroll
@@ -352,7 +381,7 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     __syncthreads();
     if (row < a.m && p1 - p0 <= kNaturalLong) {
         row_accumulate<V, G, T, U, false, UA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, p0, p1, kWave,
-                                              a.colidx, a.vals, a.B, a.ldb, colok, coff);
+                                              a.colidx, a.vals, a.B, (uint32_t)a.ldb, colok[0], coff);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
             float *dst = a.C + row * a.ldc;
@@ -369,7 +398,7 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
         row_accumulate<V, G, T, U, false, UA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, q0 + wv * kWave,
-                                              q1, kBlock, a.colidx, a.vals, a.B, a.ldb, colok, coff);
+                                              q1, kBlock, a.colidx, a.vals, a.B, (uint32_t)a.ldb, colok[0], coff);
         reduce_groups<V, G, T>(acc);
         __syncthreads();  // s_red of the previous long row has been read
         if (grp == 0) {
