@@ -54,6 +54,29 @@ struct PanelRows {
     f4 acc[RW][Q];
 };
 
+// NB visits of one row: entries jj .. jj+NB-1 of the row's window (all inside the current panel).  The LDS reads
+// of all NB entries are issued before the first multiply-add.
+template <int NB, int Q, int KR>
+__device__ __forceinline__ void panel_visits(f4 (&acc)[Q], int colreg, float valreg, int jj, const f4 *sbuf, int k0,
+                                             int lane) {
+    constexpr int kRowQuads = Q * (kPanelCols / 4);
+    f4 x[NB][Q];
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        const int c = __builtin_amdgcn_readlane(colreg, jj + u);
+#pragma unroll
+        for (int q = 0; q < Q; ++q) x[u][q] = sbuf[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
+    }
+#pragma unroll
+    for (int u = 0; u < NB; ++u) {
+        const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(valreg), jj + u));
+#pragma unroll
+        for (int q = 0; q < Q; ++q)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[q][i] = __builtin_fmaf(v, x[u][q][i], acc[q][i]);
+    }
+}
+
 // One panel's worth of work for the RW rows of a wavefront.  Columns within a row are strictly increasing
 // (checked by the planner), so a panel of kRows rows of B takes at most kRows entries of a row: they are the
 // lanes [pos, lim) of the row's 64-entry window.  A window that would be left with fewer than kRows entries is
@@ -63,7 +86,6 @@ struct PanelRows {
 template <int RW, int kBatch, int Q, int KR>
 __device__ __forceinline__ void panel_compute(PanelRows<RW, kBatch, Q> &st, const f4 *sbuf, int k0, int lane,
                                               const int32_t *colidx, const float *vals) {
-    constexpr int kRowQuads = Q * (kPanelCols / 4);
     constexpr int kRows = KR;
     const int kend = k0 + kRows;
     int lim[RW], j[RW];
@@ -84,36 +106,16 @@ __device__ __forceinline__ void panel_compute(PanelRows<RW, kBatch, Q> &st, cons
     for (int r = 0; r < RW; ++r) {
         // Whole batches first, without a test per entry (all branches here are wave-uniform, and the scalar
         // instructions of such tests cost issue slots like vector ones: this loop is bound by instruction issue), then
-        // the remaining entries one at a time.  In each step the LDS reads are issued before the multiply-adds.
+        // half a batch if that many entries are left, then the remaining entries one at a time.
         int jj = j[r];
-        for (; jj + kBatch <= lim[r]; jj += kBatch) {
-            f4 x[kBatch][Q];
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const int c = __builtin_amdgcn_readlane(st.colreg[r], jj + u);
-#pragma unroll
-                for (int q = 0; q < Q; ++q) x[u][q] = sbuf[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
-            }
-#pragma unroll
-            for (int u = 0; u < kBatch; ++u) {
-                const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.valreg[r]), jj + u));
-#pragma unroll
-                for (int q = 0; q < Q; ++q)
-#pragma unroll
-                    for (int i = 0; i < 4; ++i) st.acc[r][q][i] = __builtin_fmaf(v, x[u][q][i], st.acc[r][q][i]);
+        for (; jj + kBatch <= lim[r]; jj += kBatch) panel_visits<kBatch, Q, KR>(st.acc[r], st.colreg[r], st.valreg[r], jj, sbuf, k0, lane);
+        if constexpr (kBatch >= 4) {
+            if (jj + kBatch / 2 <= lim[r]) {
+                panel_visits<kBatch / 2, Q, KR>(st.acc[r], st.colreg[r], st.valreg[r], jj, sbuf, k0, lane);
+                jj += kBatch / 2;
             }
         }
-        for (; jj < lim[r]; ++jj) {
-            f4 x[Q];
-            const int c = __builtin_amdgcn_readlane(st.colreg[r], jj);
-#pragma unroll
-            for (int q = 0; q < Q; ++q) x[q] = sbuf[(c - k0) * kRowQuads + q * (kPanelCols / 4) + lane];
-            const float v = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(st.valreg[r]), jj));
-#pragma unroll
-            for (int q = 0; q < Q; ++q)
-#pragma unroll
-                for (int i = 0; i < 4; ++i) st.acc[r][q][i] = __builtin_fmaf(v, x[q][i], st.acc[r][q][i]);
-        }
+        for (; jj < lim[r]; ++jj) panel_visits<1, Q, KR>(st.acc[r], st.colreg[r], st.valreg[r], jj, sbuf, k0, lane);
     }
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
