@@ -161,7 +161,8 @@ typedef struct scorch_spmm_plan_info {
     uint64_t off_win_row_start, off_wave_rows, off_items, off_split, off_partials;
     uint64_t workspace_bytes_used;
     int32_t n_hot_columns; /* columns whose rows of B keep the default cache policy (0: no hot/cold split) */
-    float hot_share;       /* share of the stored entries that point at those columns */
+    float hot_share;       /* share of the stored entries that point at those columns (beyond 2^24 entries:
+                              of an evenly spread sample of 2^23..2^24 of them, which is what ranks the columns) */
 } scorch_spmm_plan_info_t;
 
 scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spmm_plan_info_t *out);

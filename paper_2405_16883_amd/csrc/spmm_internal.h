@@ -24,6 +24,7 @@ constexpr int kSliceCols = 32;  // XCD-sliced mode: 32 fp32 columns = one 128-by
 constexpr int64_t kL2SliceBudget = 2560 * 1024;  // bytes of B an XCD's 4 MB L2 is trusted to keep resident
 constexpr int64_t kMallBytes = 256ll << 20;      // memory-side cache shared by all XCDs
 constexpr int kDegBins = 32 * 16 + 1;            // column-degree histogram: 16 bins per power of two
+constexpr int64_t kHotSampleMax = 1 << 24;  // stored entries counted at most when the columns are ranked by degree
 
 // Parameters that decide how rows are classed and cut (paper has none of this; see the header).
 struct PlanParams {

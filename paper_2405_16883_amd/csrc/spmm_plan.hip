@@ -195,9 +195,17 @@ __global__ __launch_bounds__(kBlock) void plan_sorted_kernel(const int32_t *rowp
 // those rows of B with the default cache policy and all others with the streaming (nt) policy, which on this
 // hardware leaves the memory-side cache alone.
 
-// deg[c] = number of stored entries with column c.
-__global__ __launch_bounds__(kBlock) void plan_coldeg_kernel(const int32_t *colidx, int64_t nnz, int32_t k, int32_t *deg) {
-    for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p < nnz; p += (int64_t)gridDim.x * kBlock) {
+// deg[c] = number of sampled stored entries with column c.  One entry is taken out of every `stride` consecutive
+// ones (stride a power of two; 1 = all entries), at a position that varies from one group of entries to the next:
+// a fixed position would always pick the same rank within rows of a regular length, i.e. always low or always high
+// columns.  The count only ranks the columns for a cache policy, so a sample serves; the atomic additions (one
+// 32-byte memory transaction each) are what the planner spends most of its time on for a large matrix.
+__global__ __launch_bounds__(kBlock) void plan_coldeg_kernel(const int32_t *colidx, int64_t nnz, int32_t k,
+                                                             int32_t stride, int32_t *deg) {
+    const int64_t groups = (nnz + stride - 1) / stride;
+    for (int64_t g = (int64_t)blockIdx.x * kBlock + threadIdx.x; g < groups; g += (int64_t)gridDim.x * kBlock) {
+        const int64_t p = g * stride + (int64_t)((((uint32_t)g * 2654435761u) >> 16) & (uint32_t)(stride - 1));
+        if (p >= nnz) continue;
         const int c = colidx[p];
         if ((uint32_t)c < (uint32_t)k) atomicAdd(&deg[c], 1);
     }
@@ -257,9 +265,13 @@ static scorch_status_t mark_hot_columns(scorch_spmm_plan_t *plan, const int32_t 
     hipError_t e = hipMemsetAsync(deg, 0, (size_t)plan->k * 4, stream);
     if (e == hipSuccess) e = hipMemsetAsync(bins, 0, (size_t)kDegBins * 16, stream);
     if (e != hipSuccess) return hip_fail(e, "clear column degrees");
-    const uint32_t g1 = (uint32_t)std::min<int64_t>((plan->nnz + kBlock - 1) / kBlock, 256 * 64);
+    // every entry up to 2^24 of them, beyond that every 2nd, 4th, ... so that at most 2^24 are counted
+    int32_t stride = 1;
+    while ((plan->nnz + stride - 1) / stride > kHotSampleMax) stride *= 2;
+    const int64_t groups = (plan->nnz + stride - 1) / stride;
+    const uint32_t g1 = (uint32_t)std::min<int64_t>((groups + kBlock - 1) / kBlock, 256 * 64);
     const uint32_t g2 = (uint32_t)std::min<int64_t>(((int64_t)plan->k + kBlock - 1) / kBlock, 256 * 4);
-    hipLaunchKernelGGL(plan_coldeg_kernel, dim3(g1), dim3(kBlock), 0, stream, colidx, plan->nnz, plan->k, deg);
+    hipLaunchKernelGGL(plan_coldeg_kernel, dim3(g1), dim3(kBlock), 0, stream, colidx, plan->nnz, plan->k, stride, deg);
     hipLaunchKernelGGL(plan_degbins_kernel, dim3(g2), dim3(kBlock), 0, stream, deg, plan->k, bins);
     e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "launch column-degree kernels");
@@ -280,7 +292,7 @@ static scorch_status_t mark_hot_columns(scorch_spmm_plan_t *plan, const int32_t 
         min_bin = b;
     }
     plan->n_hot = 0;
-    plan->hot_share = plan->nnz > 0 ? (float)((double)entries / (double)plan->nnz) : 0.f;
+    plan->hot_share = groups > 0 ? (float)std::min(1.0, (double)entries / (double)groups) : 0.f;  // of the sampled entries
     // Worth it only when a small part of B takes a large part of the gathers (measured on the large power-law
     // workload: 5 % of the rows of B, 54 % of the gathers, 6.5 % less time).
     if (rows == 0 || (!forced && plan->hot_share < 0.25f)) return SCORCH_OK;
