@@ -333,21 +333,31 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     }
 }
 
-// Plan-free path: a workgroup takes 4 consecutive rows in natural order.  A row of up to kNaturalLong entries
-// is done by its own wavefront; a longer one by all 4 wavefronts together (interleaved 64-entry chunks, LDS tree),
-// which shortens the serial chain of a heavy row fourfold without any scratch memory.
+// Plan-free path: rows in natural order, a run of up to kNaturalRowsMax consecutive rows per wavefront (the host
+// picks the run length from m alone, so that the grid still fills the chip; nothing about the row lengths is known
+// before the launch).  A wavefront reads the row pointers of its run once (a lane per row) and then proceeds
+// greedily: the next rows, as long as they are short (up to kNaturalShort entries) and fit the LDS stage together,
+// are staged with coalesced reads and walked one row per lane group, like a window of the planned path; a longer
+// row is streamed through the stage by the whole wavefront, the lane groups taking interleaved entries; a row of
+// more than kNaturalLong entries (kNaturalMid if such rows are rare in the workgroup) is left to the end, where all 4
+// wavefronts of the workgroup take it together (interleaved 64-entry chunks, LDS tree), which shortens the serial
+// chain of a heavy row fourfold without any scratch memory.
 constexpr int kNaturalLong = 2048;
+constexpr int kNaturalMid = 256;
+constexpr int kNaturalRowsMax = 16;
+constexpr int kNaturalShort = 32;
 
 template <int V, int G, int T, int U, int NT, bool UA>
 __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) {
     using vec = typename Vec<V>::type;
+    constexpr int S = kWave / G;
     constexpr int GV = G * V;
     constexpr int TW = GV * T;
     constexpr bool NTC = (NT & 1) != 0;
-    __shared__ int s_col[kWavesPerBlock * kWave];
-    __shared__ float s_val[kWavesPerBlock * kWave];
+    __shared__ int s_raw[kWavesPerBlock * smem_ints_per_wave()];
     __shared__ float s_red[kWavesPerBlock * TW];
-    __shared__ int s_p0[kWavesPerBlock], s_p1[kWavesPerBlock];
+    __shared__ int s_long[kWavesPerBlock * kNaturalRowsMax];  // rows left to the whole workgroup
+    __shared__ int s_nlong, s_nmid;
     const int tid = threadIdx.x;
     const int wv = tid >> 6;
     const int lane = tid & 63;
@@ -356,8 +366,9 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     const uint32_t per_tile = (uint32_t)a.nb_wave;
     const uint32_t ct = blockIdx.x / per_tile;
     const uint32_t b = blockIdx.x - ct * per_tile;
-    const int64_t row0 = (int64_t)b * kWavesPerBlock;
-    const int64_t row = row0 + wv;
+    const int NR = a.rows_per_wave;
+    const int64_t r0 = ((int64_t)b * kWavesPerBlock + wv) * NR;
+    const int nr = (int)max((int64_t)0, min((int64_t)NR, (int64_t)a.m - r0));
     const int c0 = (int)ct * TW + lig * V;
     bool colok[T];
     int coff[T];  // see spmm_fused_kernel
@@ -366,39 +377,88 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
         colok[t] = (c0 + t * GV) < a.n;
         coff[t] = min(c0 + t * GV, a.n - V);
     }
+    const uint32_t ldb = (uint32_t)a.ldb;
+    int *lcol = s_raw + wv * smem_ints_per_wave();
+    float *lval = reinterpret_cast<float *>(lcol + kStageMax);
+    int *lrp = lcol + 2 * kStageMax;
     vec acc[T];
-#pragma unroll
-    for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-    int p0 = 0, p1 = 0;
-    if (row < a.m) {
-        p0 = a.rowptr[row];
-        p1 = a.rowptr[row + 1];
-    }
-    if (lane == 0) {
-        s_p0[wv] = p0;
-        s_p1[wv] = p1;
+    if (tid == 0) {
+        s_nlong = 0;
+        s_nmid = 0;
     }
     __syncthreads();
-    if (row < a.m && p1 - p0 <= kNaturalLong) {
-        row_accumulate<V, G, T, U, false, UA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, p0, p1, kWave,
-                                              a.colidx, a.vals, a.B, (uint32_t)a.ldb, colok[0], coff);
-        reduce_groups<V, G, T>(acc);
-        if (grp == 0) {
-            float *dst = a.C + row * a.ldc;
+    const int rpv = nr > 0 ? a.rowptr[r0 + min(lane, nr)] : 0;
+    const int rnext = __shfl_down(rpv, 1, kWave);  // lanes past the run hold the last pointer; lane 63 is never a row
+    // Rows of more than kNaturalMid entries: outliers of a graph if the workgroup has one or two of them (then all 4
+    // wavefronts take each of them together), the normal case of a matrix with long rows if it has more (then every
+    // wavefront keeps its own rows, up to kNaturalLong entries)
+    const int nmid = (int)__builtin_popcountll(__ballot(lane < nr && rnext - rpv > kNaturalMid));
+    if (lane == 0 && nmid > 0) atomicAdd(&s_nmid, nmid);
+    __syncthreads();
+    const int long_limit = s_nmid <= 2 ? kNaturalMid : kNaturalLong;
+    if (nr > 0) {
+        lrp[lane] = rpv;
+        wave_lds_sync();
+        int i = 0;
+        while (i < nr) {
+            const int base = lrp[i];
+            // rows i .. j-1: the longest run of short rows (one lane group walks a row alone, so only rows of up to
+            // kNaturalShort entries qualify) that fits the stage
+            const bool stops = lane >= i && (lane >= nr || rnext - rpv > kNaturalShort || rnext - base > kStageMax);
+            const int j = __builtin_ctzll(__ballot(stops));  // lane nr always stops
+            if (j == i) {
+                const int p1 = lrp[i + 1];
+                if (p1 - base <= long_limit) {
 #pragma unroll
-            for (int t = 0; t < T; ++t)
-                if (colok[t])
-                    vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(acc[t], a.bias ? a.bias + coff[t] : nullptr, a.act));
+                    for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
+                    row_accumulate<V, G, T, U, false, UA>(acc, lcol, lval, lane, grp, base, p1, kWave, a.colidx, a.vals,
+                                                          a.B, ldb, colok[0], coff);
+                    reduce_groups<V, G, T>(acc);
+                    if (grp == 0) {
+                        float *dst = a.C + (r0 + i) * a.ldc;
+#pragma unroll
+                        for (int t = 0; t < T; ++t)
+                            if (colok[t])
+                                vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(acc[t], a.bias ? a.bias + coff[t] : nullptr, a.act));
+                    }
+                } else if (lane == 0) {
+                    s_long[atomicAdd(&s_nlong, 1)] = (int)(r0 + i);
+                }
+                ++i;
+                continue;
+            }
+            const int cnt = min(lrp[j] - base, kStageMax);
+            for (int e = lane; e < cnt; e += kWave) {
+                lcol[e] = a.colidx[base + e];
+                lval[e] = a.vals[base + e];
+            }
+            wave_lds_sync();
+            for (int ri = i + grp; ri < j; ri += S) {
+#pragma unroll
+                for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
+                gather_fma<V, T, U, UA>(acc, lcol, lval, lrp[ri] - base, lrp[ri + 1] - base, 1, a.B, ldb, colok[0], coff);
+                float *dst = a.C + (r0 + ri) * a.ldc;
+#pragma unroll
+                for (int t = 0; t < T; ++t)
+                    if (colok[t])
+                        vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(acc[t], a.bias ? a.bias + coff[t] : nullptr, a.act));
+            }
+            wave_lds_sync();  // the stage is refilled next
+            i = j;
         }
     }
-    // long rows of this workgroup, one after the other, all wavefronts on each (the loop is workgroup-uniform)
-    for (int w = 0; w < kWavesPerBlock; ++w) {
-        const int q0 = s_p0[w], q1 = s_p1[w];
-        if (q1 - q0 <= kNaturalLong) continue;
+    __syncthreads();
+    // long rows of this workgroup, one after the other, all wavefronts on each (the loop is workgroup-uniform; the
+    // order of the list varies from run to run, the result of each row does not depend on it)
+    const int nlong = s_nlong;
+    for (int w = 0; w < nlong; ++w) {
+        const int64_t row = s_long[w];
+        const int q0 = a.rowptr[row], q1 = a.rowptr[row + 1];
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-        row_accumulate<V, G, T, U, false, UA>(acc, s_col + wv * kWave, s_val + wv * kWave, lane, grp, q0 + wv * kWave,
-                                              q1, kBlock, a.colidx, a.vals, a.B, (uint32_t)a.ldb, colok[0], coff);
+        // twice the gathers in flight: these rows are few, and the longest of them is the serial chain of the launch
+        row_accumulate<V, G, T, 2 * U, false, UA>(acc, lcol, lval, lane, grp, q0 + wv * kWave, q1, kBlock, a.colidx,
+                                                  a.vals, a.B, ldb, colok[0], coff);
         reduce_groups<V, G, T>(acc);
         __syncthreads();  // s_red of the previous long row has been read
         if (grp == 0) {
@@ -412,7 +472,7 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
         }
         __syncthreads();
         if (wv == 0 && grp == 0) {
-            float *dst = a.C + (row0 + w) * a.ldc;
+            float *dst = a.C + row * a.ldc;
 #pragma unroll
             for (int t = 0; t < T; ++t) {
                 if (!colok[t]) continue;
@@ -678,7 +738,10 @@ scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, cons
     a.ldc = ldc;
     a.m = m;
     a.n = n;
-    a.nb_wave = (int32_t)ceil_div64(m, kWavesPerBlock);
+    // rows per wavefront: 4 once that leaves a workgroup for every compute unit (measured: 1, 2, 4, 8, 16 rows on the
+    // five benchmark workloads; 4 is within 1 % of the best of each that has 16 384 rows or more)
+    a.rows_per_wave = (int32_t)std::min<int64_t>(4, std::max<int64_t>(1, m / 4096));
+    a.nb_wave = (int32_t)ceil_div64(m, (int64_t)kWavesPerBlock * a.rows_per_wave);
     a.ncoltiles = mp.ncoltiles;
     const int64_t grid = (int64_t)a.nb_wave * mp.ncoltiles;
     if (grid > 0x7fffffffLL) {

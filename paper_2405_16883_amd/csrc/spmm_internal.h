@@ -79,6 +79,7 @@ struct ExecArgs {
     const float *bias;      // epilogue: n floats added to every row of C, or nullptr
     int32_t act;            // epilogue: 0 identity, 1 ReLU
     const uint32_t *hotmask;  // one bit per column of A, set for the most referenced rows of B (hot/cold variants only)
+    int32_t rows_per_wave;    // plan-free kernel only: consecutive rows taken by one wavefront
 };
 
 struct PanelArgs {
