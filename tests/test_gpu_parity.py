@@ -186,6 +186,31 @@ def test_edge_shapes(name):
         run_both(integer_valued(p, seed=12), exact=True, label=f"{name} n={n} k={k} int")
 
 
+@pytest.mark.parametrize("n", [1, 33, 128, 300])
+def test_plan_free_row_runs(n):
+    """With 16 384 rows or more the plan-free kernel gives a wavefront a run of 4 consecutive rows: short rows are staged
+    together (at most 320 entries, rows of up to 32), longer ones streamed, rows beyond 256 / 2 048 entries left to
+    the whole workgroup depending on how many of them the workgroup has.  Row lengths sit on every one of these limits,
+    in runs that mix them, in a matrix whose last workgroup is ragged."""
+    rng = np.random.default_rng(21)
+    m = 16384 + 37
+    lens = rng.integers(0, 41, size=m)
+    special = [0, 1, 31, 32, 33, 64, 255, 256, 257, 287, 288, 289, 319, 320, 321, 2047, 2048, 2049, 3000]
+    for i, pos in enumerate(range(5, m - 64, 211)):
+        lens[pos] = special[i % len(special)]
+    lens[1000:1016] = 20  # a run of 16 rows = 4 wavefronts x 4 rows whose stages are exactly full (80 entries each)
+    lens[2000:2004] = [80, 80, 80, 80]  # 320 entries: the largest stage
+    lens[3000:3016] = 300  # a workgroup with many rows beyond 256 entries: every wavefront keeps its own
+    lens[4000:4016] = [0] * 15 + [257]  # a single such row in a workgroup: taken by the 4 wavefronts together
+    lens[m - 3:] = [2049, 0, 33]
+    p = csr_from_row_lengths(lens.tolist(), 5000, n, seed=22, duplicates=True, sorted_cols=False)
+    d = DeviceProblem(p)
+    check_against_oracle(p, d.run_natural(), d.ldc, label=f"plan-free row runs n={n}")
+    q = integer_valued(p, seed=23)
+    dq = DeviceProblem(q)
+    check_against_oracle(q, dq.run_natural(), dq.ldc, exact=True, label=f"plan-free row runs n={n} int")
+
+
 def test_single_row_with_very_many_entries():
     # integer case: |partial sums| <= 4*8*500000 = 1.6e7 < 2^24, so every summation order is exact
     p = integer_valued(csr_from_row_lengths([500_000, 2, 0], 50_000, 128, seed=13, duplicates=True), seed=13)
