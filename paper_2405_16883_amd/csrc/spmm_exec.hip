@@ -639,10 +639,29 @@ static kernel_fn pick_fused_hot(int G, int T) {
         default: return spmm_fused_kernel<4, 64, 1, 8, 1, false, true>;
     }
 }
-static kernel_fn pick_natural(int V, int G, int T, int U, int NT, bool UA) {
-    U = 8;  // the plan-free path is compiled for one unroll depth and streaming stores only
-    NT = 1;
-    SCORCH_PICK(spmm_natural_kernel)
+// The plan-free path is compiled for one unroll depth (8) and streaming stores only.
+#define SCORCH_NATURAL(V, G, T, UA) return spmm_natural_kernel<V, G, T, 8, 1, UA>;
+#define SCORCH_NATURAL_G4(UA)                                               \
+    if (T == 2) { SCORCH_NATURAL(4, 64, 2, UA) }                            \
+    switch (G) {                                                            \
+        case 1: SCORCH_NATURAL(4, 1, 1, UA)                                 \
+        case 2: SCORCH_NATURAL(4, 2, 1, UA)                                 \
+        case 4: SCORCH_NATURAL(4, 4, 1, UA)                                 \
+        case 8: SCORCH_NATURAL(4, 8, 1, UA)                                 \
+        case 16: SCORCH_NATURAL(4, 16, 1, UA)                               \
+        case 32: SCORCH_NATURAL(4, 32, 1, UA)                               \
+        default: SCORCH_NATURAL(4, 64, 1, UA)                               \
+    }
+static kernel_fn pick_natural(int V, int G, int T, bool UA) {
+    if (V == 4) {
+        if (UA) { SCORCH_NATURAL_G4(true) } else { SCORCH_NATURAL_G4(false) }
+    }
+    if (V == 2) { SCORCH_NATURAL(2, 1, 1, false) }
+    switch (G) {
+        case 1: SCORCH_NATURAL(1, 1, 1, false)
+        case 2: SCORCH_NATURAL(1, 2, 1, false)
+        default: SCORCH_NATURAL(1, 4, 1, false)
+    }
 }
 
 static inline int64_t ceil_div64(int64_t a, int64_t b) { return (a + b - 1) / b; }
@@ -726,7 +745,7 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
 
 scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
-                               int32_t U, int32_t NT, hipStream_t stream) {
+                               hipStream_t stream) {
     const Mapping mp = pick_mapping(n, B, ldb, C, ldc, false);
     ExecArgs a{};
     a.rowptr = rowptr;
@@ -748,7 +767,7 @@ scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, cons
         set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);
         return SCORCH_ERR_UNSUPPORTED;
     }
-    kernel_fn fn = pick_natural(mp.V, mp.G, mp.T, U, NT, mp.UA);
+    kernel_fn fn = pick_natural(mp.V, mp.G, mp.T, mp.UA);
     hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "launch spmm_natural_kernel");

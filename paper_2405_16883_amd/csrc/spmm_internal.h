@@ -203,6 +203,6 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
 
 scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
-                               int32_t U, int32_t NT, hipStream_t stream);
+                               hipStream_t stream);
 
 }  // namespace scorch
