@@ -127,6 +127,68 @@ def time_sddmm(res, torch, sp, d, steps=30, warmup=5):
             "frac_hbm": bytes_min / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
 
 
+def _event_ms(torch, call, steps, warmup):
+    for _ in range(warmup):
+        call()
+    torch.cuda.synchronize()
+    ev = []
+    for _ in range(steps):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        call()
+        b.record()
+        ev.append((a, b))
+    torch.cuda.synchronize()
+    return float(np.mean([a.elapsed_time(b) for a, b in ev]))
+
+
+def time_widenings(res, torch, sp, steps=30, warmup=5):
+    """Short timings, on the resident pattern, of the paths built around the SpMM: SpMV (n = 1, its own plan), the
+    fused bias + ReLU epilogue (against the same call without it), and the row-pointer build from a coordinate list
+    and from doubly compressed rows.  Bytes are the minimum-traffic model of each call."""
+    p = res.p
+    dev = "cuda:0"
+    out = {}
+    g = torch.Generator(device=dev).manual_seed(2)
+    # SpMV: y = A x
+    x = torch.randn((p.k, 1), generator=g, dtype=torch.float32, device=dev)
+    y = torch.empty((p.m, 1), dtype=torch.float32, device=dev)
+    plan1 = sp.scorch_spmm_plan(p.m, p.k, 1, res.rowptr, p.nnz, colidx=res.colidx)
+    ms = _event_ms(torch, lambda: sp.scorch_spmm_csr_planned(plan1, res.rowptr, res.colidx, res.vals, x, y), steps, warmup)
+    plan1.destroy()
+    uniq = int(np.count_nonzero(np.bincount(p.colidx, minlength=p.k))) if p.nnz else 0
+    b = p.nnz * 8 + (p.m + 1) * 4 + p.m * 4 + uniq * 4
+    out["spmv"] = {"event_ms_mean": ms, "gflops": 2.0 * p.nnz / (ms * 1e-3) / 1e9, "bytes_min": b,
+                   "frac_hbm": b / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS}
+    # fused epilogue: C = relu(A B + bias)
+    bias = torch.randn(p.n, generator=g, dtype=torch.float32, device=dev)
+    ms_e = _event_ms(torch, lambda: sp.scorch_spmm_csr_planned_epilogue(res.plan, res.rowptr, res.colidx, res.vals, res.B,
+                                                                         bias, 1, res.C), steps, warmup)
+    ms_p = _event_ms(torch, res.step, steps, warmup)
+
+    def unfused():
+        res.step()
+        res.C.add_(bias).relu_()
+    ms_u = _event_ms(torch, unfused, steps, warmup)
+    out["epilogue"] = {"fused_event_ms_mean": ms_e, "plain_spmm_event_ms_mean": ms_p,
+                       "spmm_then_elementwise_event_ms_mean": ms_u}
+    # second storage formats: row pointers from sorted row coordinates / from the list of stored rows
+    rows = torch.repeat_interleave(torch.arange(p.m, dtype=torch.int32, device=dev),
+                                   (res.rowptr[1:] - res.rowptr[:-1]).long())
+    rp = torch.empty(p.m + 1, dtype=torch.int32, device=dev)
+    ms_c = _event_ms(torch, lambda: sp.scorch_coo_to_csr_rowptr(p.m, rows, rp), steps, warmup)
+    ok_c = bool(torch.equal(rp, res.rowptr))
+    lens = res.rowptr[1:] - res.rowptr[:-1]
+    ids = torch.nonzero(lens > 0).flatten().to(torch.int32)
+    pos = torch.cat([res.rowptr[:-1][ids.long()], res.rowptr[-1:]]).to(torch.int32)
+    ms_d = _event_ms(torch, lambda: sp.scorch_dcsr_to_csr_rowptr(p.m, ids, pos, rp), steps, warmup)
+    ok_d = bool(torch.equal(rp, res.rowptr))
+    bc = p.nnz * 4 + (p.m + 1) * 4
+    out["formats"] = {"coo_rowptr_event_ms_mean": ms_c, "coo_frac_hbm": bc / (ms_c * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                      "coo_matches_rowptr": ok_c, "dcsr_rowptr_event_ms_mean": ms_d, "dcsr_matches_rowptr": ok_d}
+    return out
+
+
 def time_graph_replay(res, torch, sp, steps_per_graph=20, replays=10):
     """Per-step time when `steps_per_graph` planned calls are recorded into one HIP graph (launch overhead amortised)."""
     side = torch.cuda.Stream()
@@ -315,9 +377,17 @@ def main():
                 o["sddmm"] = time_sddmm(r, torch, sp, 128)
                 log(f"[bench] sddmm on cfg 3 pattern, d=128: {o['sddmm']['event_ms_mean']:.4f} ms  {o['sddmm']['gflops']:.0f} GFLOP/s  "
                     f"{100 * o['sddmm']['frac_hbm']:.1f}% of HBM peak (min-traffic model)")
+                o["widenings"] = time_widenings(r, torch, sp)
+                w = o["widenings"]
+                log(f"[bench] on cfg 3 pattern: spmv {w['spmv']['event_ms_mean'] * 1e3:.1f} us ({100 * w['spmv']['frac_hbm']:.1f}% of HBM peak); "
+                    f"spmm+bias+relu fused {w['epilogue']['fused_event_ms_mean'] * 1e3:.1f} us, plain spmm "
+                    f"{w['epilogue']['plain_spmm_event_ms_mean'] * 1e3:.1f} us, spmm then elementwise "
+                    f"{w['epilogue']['spmm_then_elementwise_event_ms_mean'] * 1e3:.1f} us; rowptr from coo "
+                    f"{w['formats']['coo_rowptr_event_ms_mean'] * 1e3:.1f} us (ok {w['formats']['coo_matches_rowptr']}), from dcsr "
+                    f"{w['formats']['dcsr_rowptr_event_ms_mean'] * 1e3:.1f} us (ok {w['formats']['dcsr_matches_rowptr']})")
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
                                                            "gbs_min_traffic", "frac_hbm", "cold_event_ms_mean",
-                                                           "cold_frac_hbm", "plan_ms", "plan_free_event_ms_mean") + (("sddmm",) if "sddmm" in o else ())
+                                                           "cold_frac_hbm", "plan_ms", "plan_free_event_ms_mean") + tuple(x for x in ("sddmm", "widenings") if x in o)
                                         + tuple(x for x in ("mode", "traffic", "alu_roofline") if x in o)
                                         + (("graph_replay_ms_per_step",) if "graph_replay_ms_per_step" in o else ())}
             del r
