@@ -123,6 +123,32 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
                                                bool active, const int (&boff)[T],
                                                const uint32_t *hotmask = nullptr) {
     constexpr int S = kWave / G;
+    if constexpr (G == 1 && T == 1 && !HOT) {
+        // One-lane groups (n <= 4): every lane owns the entries pfirst + lane + i * stride and needs no broadcast, so
+        // the stage is skipped: U index/value pairs are read straight into registers, then U gathers are issued.  A row
+        // of up to 64 U entries costs two memory round trips instead of two per 64 entries.  The order in which a lane
+        // adds its products is the same as with the stage.
+        using vec = typename Vec<V>::type;
+        if (!active) return;
+        const float *base = Bc + boff[0];
+        for (int pb = pfirst + lane; pb - lane < p1; pb += stride * U) {
+            int c[U];
+            float v[U];
+            vec x[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int p = pb + u * stride;
+                const bool ok = p < p1;
+                c[u] = ok ? ld_idx<NTA>(colidx + p) : 0;
+                v[u] = ok ? ld_val<NTA>(vals + p) : 0.f;
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) x[u] = pb + u * stride < p1 ? vload<V, UA>(b_row(base, c[u], ldb)) : vzero<V>();
+#pragma unroll
+            for (int u = 0; u < U; ++u) vfma<V>(acc[0], v[u], x[u]);
+        }
+        return;
+    }
     int pc = pfirst + lane;
     int cn = 0;
     float vn = 0.f;
