@@ -54,10 +54,12 @@ enum {
 typedef struct scorch_spmm_plan_s scorch_spmm_plan_t; /* small host-side handle */
 
 /*
- * Plan-free SpMM: C = A.B in natural row order, one wavefront per row and the four wavefronts
- * of a workgroup together on rows with more than 2048 entries.  Always available and correct for
- * any valid input; no load balancing beyond that, so a row with very many entries still runs
- * on a single workgroup.  (Definition: see the top of this file.)
+ * Plan-free SpMM: C = A.B in natural row order.  A wavefront takes a short run of consecutive rows
+ * (up to 4), walks the short ones (up to 32 entries) side by side and streams the longer ones; the
+ * four wavefronts of a workgroup work together on rows with more than 2048 entries (more than 256
+ * where such rows are rare).  Always available and correct for any valid input; no load balancing
+ * beyond that, so a row with very many entries still runs on a single workgroup.  (Definition: see
+ * the top of this file.)
  */
 scorch_status_t scorch_spmm_csr(int32_t m, int32_t k, int32_t n,
                                 const int32_t *rowptr, const int32_t *colidx, const float *vals,
