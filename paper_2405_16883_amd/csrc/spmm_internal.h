@@ -19,7 +19,6 @@ constexpr int kStageMax = kBNMax + kLWMax;
 constexpr int kWindowRowsMax = 64;  // one lane per row when reading rowptr
 constexpr int kXcds = 8;        // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
 constexpr int kPanelCols = 256; // panel kernel: one wavefront covers 256 columns (64 lanes x float4)
-constexpr int kPanelRows = 64;  // panel kernel: B rows per LDS panel (64 x 1 KB = 64 KB)
 constexpr int kSliceCols = 32;  // XCD-sliced mode: 32 fp32 columns = one 128-byte line of a B row
 constexpr int64_t kL2SliceBudget = 2560 * 1024;  // bytes of B an XCD's 4 MB L2 is trusted to keep resident
 constexpr int64_t kMallBytes = 256ll << 20;      // memory-side cache shared by all XCDs
@@ -37,7 +36,7 @@ struct PlanParams {
     int32_t NT;     // bit 0: streaming (non-temporal) stores for C
     int32_t SLICED; // 1: the workload suits XCD-sliced execution (see want_sliced)
     int32_t PACK;   // 1: sliced execution gathers from a slice-major copy of B made at every call
-    int32_t PANEL;  // 1: dense-ish sorted rows: stream B through LDS in k-panels (spmm_panel.hip)
+    int32_t PANEL;  // dense-ish sorted rows: stream B through LDS in k-panels (spmm_panel.hip); 1: 256-column tiles, 2: 512
     int32_t HOT;    // >0: budget in KB for the most referenced rows of B, which alone keep the default cache policy
 };
 
