@@ -610,16 +610,6 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
     return mp;
 }
 
-// Number of workgroups for `per_tile` units of row work per column tile (see tile_of_workgroup).
-int64_t xcd_grid_size(int32_t xcd_slices, int32_t ncoltiles, int64_t per_tile) {
-    if (xcd_slices == 0) return per_tile * ncoltiles;
-    int64_t q = (int64_t)(ncoltiles / kXcds) * per_tile;
-    const int rest = ncoltiles % kXcds;
-    for (int s = kXcds / 2; s >= 1; s >>= 1)
-        if (rest & s) q += (per_tile * s + kXcds - 1) / kXcds;
-    return q * kXcds;
-}
-
 static int64_t grid_size(const Mapping &mp, int64_t per_tile) {
     return xcd_grid_size(mp.xcd_slices, mp.ncoltiles, per_tile);
 }

@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "scorch_spmm.h"
+#include "xcd_map.h"
 
 namespace scorch {
 
@@ -17,7 +18,6 @@ constexpr int kBNMax = 256;
 constexpr int kLWMax = 64;
 constexpr int kStageMax = kBNMax + kLWMax;
 constexpr int kWindowRowsMax = 64;  // one lane per row when reading rowptr
-constexpr int kXcds = 8;        // accelerator dies, each with its own L2; workgroups are dealt to them round-robin
 constexpr int kPanelCols = 256; // panel kernel: one wavefront covers 256 columns (64 lanes x float4)
 constexpr int kSliceCols = 32;  // XCD-sliced mode: 32 fp32 columns = one 128-byte line of a B row
 constexpr int64_t kL2SliceBudget = 2560 * 1024;  // bytes of B an XCD's 4 MB L2 is trusted to keep resident
@@ -107,51 +107,10 @@ struct FixupArgs {
 };
 
 #if defined(__HIPCC__)
-// Which column tile and which unit of row work a workgroup owns.
-//
-// Default: tile-major (all row work of column tile 0, then tile 1, ...).
-// XCD-sliced (xcd_slices != 0): workgroups are dealt to the 8 XCDs round-robin by index, and each XCD has its own
-// L2.  Every XCD is therefore given its own narrow column slices of B, one after the other, so that the slice it is
-// gathering from stays resident in that XCD's L2.  The slices are taken in rounds: first whole rounds of 8 slices,
-// one per XCD; then the remaining r < 8 slices in groups of 4, 2 and 1 (the binary digits of r), a group of s slices
-// being shared by all 8 XCDs, 8/s XCDs per slice, which split that slice's row work between them.  Every round keeps
-// all XCDs equally busy whatever the number of slices.  The mapping only steers locality; any assignment of workgroups
-// to XCDs gives the same result.
 __device__ __forceinline__ bool tile_of_workgroup(int32_t xcd_slices, int32_t ncoltiles, uint32_t per_tile, uint32_t &ct,
                                                   uint32_t &b) {
-    if (xcd_slices == 0) {
-        ct = blockIdx.x / per_tile;
-        b = blockIdx.x - ct * per_tile;
-        return true;
-    }
-    const uint32_t xcd = blockIdx.x & (kXcds - 1);
-    uint32_t q = blockIdx.x / kXcds;
-    const uint32_t rounds = (uint32_t)ncoltiles / kXcds, rest = (uint32_t)ncoltiles % kXcds;
-    if (q < rounds * per_tile) {
-        const uint32_t round = q / per_tile;
-        b = q - round * per_tile;
-        ct = xcd + kXcds * round;
-        return true;
-    }
-    q -= rounds * per_tile;
-    uint32_t base = rounds * kXcds;
-#pragma unroll
-    for (uint32_t s = kXcds / 2; s >= 1; s >>= 1) {
-        if (rest & s) {
-            const uint32_t share = kXcds / s;  // XCDs per slice of this group
-            const uint32_t nq = (per_tile + share - 1) / share;
-            if (q < nq) {
-                ct = base + xcd % s;
-                b = q * share + xcd / s;
-                return b < per_tile;
-            }
-            q -= nq;
-            base += s;
-        }
-    }
-    return false;
+    return tile_of_index(blockIdx.x, xcd_slices, ncoltiles, per_tile, ct, b);
 }
-
 #endif
 
 }  // namespace scorch
@@ -187,7 +146,6 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
                                const float *bias, int32_t act, hipStream_t stream);
 scorch_status_t launch_pack_b(const float *B, int64_t ldb, int32_t k, int32_t n, int32_t W, float *Bp,
                               hipStream_t stream);
-int64_t xcd_grid_size(int32_t xcd_slices, int32_t ncoltiles, int64_t per_tile);
 
 // spmm_panel.hip
 bool panel_operands_ok(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc);
