@@ -573,7 +573,7 @@ struct Mapping {
     int xcd_slices;  // 0: tile-major grid; 1: column slices dealt over the XCDs (see tile_of_workgroup)
 };
 
-static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc, bool sliced) {
+static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float *C, int64_t ldc, int slice_cols) {
     Mapping mp{};
     const uintptr_t pb = reinterpret_cast<uintptr_t>(B), pc = reinterpret_cast<uintptr_t>(C);
     if (n % 4 == 0 && ldb % 4 == 0 && ldc % 4 == 0 && pb % 16 == 0 && pc % 16 == 0) mp.V = 4;
@@ -584,11 +584,11 @@ static Mapping pick_mapping(int32_t n, const float *B, int64_t ldb, const float 
     } else if (n % 2 == 0 && ldb % 2 == 0 && ldc % 2 == 0 && pb % 8 == 0 && pc % 8 == 0) mp.V = 2;
     else mp.V = 1;
     mp.xcd_slices = 0;
-    if (sliced && mp.V == 4 && !mp.UA) {
-        // 32-column (one 128-byte line) slices of B, one slice per XCD at a time
-        mp.G = kSliceCols / 4;
+    if (slice_cols > 0 && mp.V == 4 && !mp.UA) {
+        // column slices of B (32 columns = one 128-byte line of a row, or 64 or 128), one slice per XCD at a time
+        mp.G = slice_cols / 4;
         mp.T = 1;
-        mp.ncoltiles = (n + kSliceCols - 1) / kSliceCols;
+        mp.ncoltiles = (n + slice_cols - 1) / slice_cols;
         mp.xcd_slices = 1;
         return mp;
     }
@@ -687,7 +687,7 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
                                const float *bias, int32_t act, hipStream_t stream) {
     if (plan->params.PANEL && panel_operands_ok(plan->n, B, ldb, C, ldc))
         return launch_panel(plan, rowptr, colidx, vals, B, ldb, C, ldc, bias, act, stream);
-    const Mapping mp = pick_mapping(plan->n, B, ldb, C, ldc, plan->params.SLICED != 0);
+    const Mapping mp = pick_mapping(plan->n, B, ldb, C, ldc, plan->params.SLICED);
     ExecArgs a{};
     a.rowptr = rowptr;
     a.colidx = colidx;
@@ -762,7 +762,7 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
 scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                hipStream_t stream) {
-    const Mapping mp = pick_mapping(n, B, ldb, C, ldc, false);
+    const Mapping mp = pick_mapping(n, B, ldb, C, ldc, 0);
     ExecArgs a{};
     a.rowptr = rowptr;
     a.colidx = colidx;

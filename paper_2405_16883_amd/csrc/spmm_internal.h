@@ -34,7 +34,7 @@ struct PlanParams {
     int32_t BCH;    // block rows: pieces of at most BCH entries
     int32_t U;      // gathers in flight per lane group (4 or 8)
     int32_t NT;     // bit 0: streaming (non-temporal) stores for C
-    int32_t SLICED; // 1: the workload suits XCD-sliced execution (see want_sliced)
+    int32_t SLICED; // >0: XCD-sliced execution with this many columns of B per slice (32, 64 or 128; see want_sliced)
     int32_t PACK;   // 1: sliced execution gathers from a slice-major copy of B made at every call
     int32_t PANEL;  // dense-ish sorted rows: stream B through LDS in k-panels (spmm_panel.hip); 1: 256-column tiles, 2: 512
     int32_t HOT;    // >0: budget in KB for the most referenced rows of B, which alone keep the default cache policy

@@ -377,11 +377,22 @@ static int32_t pow2_floor(int64_t x) {
 // is cheap next to the gathers (8 bytes of A against 128 bytes of B per entry and slice).  Measured on uniform random
 // patterns: 164 entries per row, B 8-32 MB: 1.3-2.1x faster than the plain gather; 82 entries, B 8-33 MB: 1.0-1.5x;
 // 65 entries: even; 33-41 entries: 1.2-1.4x slower; B of 4 MB (mostly L2-resident anyway): 1.1-1.3x slower.
-static bool want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n) {
-    if (m <= 0 || n % 4 != 0 || n < 2 * kSliceCols) return false;
+// Beyond that: the 128-byte slices still win over whole rows when a slice is a few times larger than an XCD's L2
+// (uniform patterns and a power-law graph with 100-164 entries per row, slices of 4-13 MB: 1.1-2.3x faster; a
+// 17 MB slice: 1.1x slower), and with shorter rows 256-byte slices do (an XCD's L2 then keeps twice to sixteen times
+// as many rows of B as with whole rows, and a wavefront has 4 rows of B in flight per load): power-law graphs of
+// 50 k to 1 M nodes, 5 to 100 entries per row, n = 128 to 1024 in multiples of 64: 5-30 % less time than whole rows
+// (one case of 21: 1 %); uniform and pruned patterns outside the 128-byte rule: 0-43 % less; n = 160: 0-16 % less;
+// n = 96, 100, 132: 4-30 % more, hence the multiple of 64.  Returns the columns per slice (0 = whole rows).
+static int32_t want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n, bool hot_candidate) {
+    if (m <= 0 || n % 4 != 0 || n < 2 * kSliceCols) return 0;
     const int64_t slice_bytes = (int64_t)k * kSliceCols * 4;
     const int64_t b_bytes = (int64_t)k * n * 4;
-    return slice_bytes <= kL2SliceBudget && b_bytes >= 8ll << 20 && nnz / m >= 64;
+    if (b_bytes < 8ll << 20) return 0;
+    if (slice_bytes <= kL2SliceBudget && nnz / m >= 64) return kSliceCols;
+    if (hot_candidate) return 0;  // the hot/cold split needs whole rows
+    if (slice_bytes <= 13ll << 20 && nnz / m >= 64) return kSliceCols;
+    return (n >= 128 && n % 64 == 0) ? 64 : 0;
 }
 
 // The panel kernel (spmm_panel.hip) streams all of B through LDS once per block of 64 rows of A, a cost that does
@@ -415,17 +426,22 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     const int32_t bn_cap = n <= 32 ? kBNMax : 128;
     p.BN = std::min<int32_t>(bn_cap, std::max<int32_t>(16, pow2_floor(std::max<int64_t>(1, (nnz + (int64_t)p.ALPHA * m) / 4096))));
     p.LW = 32;
-    p.SLICED = want_sliced(m, k, nnz, n) ? 1 : 0;
-    if (t.sliced >= 0) p.SLICED = t.sliced != 0 && n % 4 == 0;
+    // B several times larger than the memory-side cache: see build_plan (hot columns).
+    const bool hot_candidate = (int64_t)k * n * 4 > 3 * kMallBytes && n >= 96 && nnz >= 4 * (int64_t)k;
+    p.SLICED = want_sliced(m, k, nnz, n, hot_candidate);
+    if (t.sliced >= 0) {  // 0: off, 1: the default width, 32 / 64 / 128: that many columns per slice
+        const int32_t cols = t.sliced == 1 ? kSliceCols : t.sliced;
+        p.SLICED = ((cols == 32 || cols == 64 || cols == 128) && n % 4 == 0) ? cols : 0;
+    }
     // A row stride of B above 512 bytes scatters a 128-byte column slice over few L2 sets; gather from a
     // dense slice-major copy instead (costs one read and one write of B per call).
-    p.PACK = (p.SLICED && n > 128) ? 1 : 0;
-    if (t.pack >= 0) p.PACK = (p.SLICED && t.pack != 0) ? 1 : 0;
+    p.PACK = (p.SLICED == kSliceCols && n > 128) ? 1 : 0;
+    if (t.pack >= 0) p.PACK = (p.SLICED == kSliceCols && t.pack != 0) ? 1 : 0;
     p.PANEL = want_panel(m, k, nnz, n);
     if (t.panel >= 0) p.PANEL = (t.panel > 0 && n % 4 == 0 && k > 0) ? t.panel : 0;
     // Enough independent wavefront tasks to fill 256 CUs several times over, but pieces long
     // enough that the per-piece overhead stays small.
-    const int64_t coltiles = p.SLICED ? (n + kSliceCols - 1) / kSliceCols : std::max<int64_t>(1, (n + 511) / 512);
+    const int64_t coltiles = p.SLICED ? (n + p.SLICED - 1) / p.SLICED : std::max<int64_t>(1, (n + 511) / 512);
     const int32_t ch_cap = p.SLICED ? 4096 : 1024;
     p.CH = std::min<int32_t>(ch_cap, std::max<int32_t>(256, pow2_floor(std::max<int64_t>(1, nnz * coltiles / 32768))));
     p.U = 8;
@@ -434,7 +450,7 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     // cache.  Measured on the large power-law pattern: B 3.8x / 4.9x / 9.8x the cache: 5-6 % less time; 2.4x: 4 % more;
     // 1.2x: 57 % more (the cache then holds most of B anyway and the streaming policy forfeits that).
     // Rows of B narrower than three cache lines lose with it on every pattern tried (n = 64: 4-18 % more time).
-    p.HOT = ((int64_t)k * n * 4 > 3 * kMallBytes && n >= 96 && nnz >= 4 * (int64_t)k) ? (int32_t)(kMallBytes / 4 / 1024) : 0;
+    p.HOT = (hot_candidate && p.SLICED == 0) ? (int32_t)(kMallBytes / 4 / 1024) : 0;
     if (t.hot >= 0) p.HOT = t.hot;
     if (t.bn > 0) p.BN = t.bn;
     if (t.alpha > 0) p.ALPHA = t.alpha;
