@@ -94,11 +94,13 @@ def test_base_pointers_at_float_alignment_only():
 
 @pytest.mark.parametrize("n", [64, 96, 128, 160, 256, 288, 544, 1024])
 def test_xcd_sliced_column_mapping(n):
-    """Forces the XCD-sliced grid (32-column slices dealt over the 8 XCDs) on shapes with 2..32 slices."""
+    """Forces the XCD-sliced grid (32-, 64- and 128-column slices dealt over the 8 XCDs) on shapes with 1..32 slices,
+    the last one ragged where n is no multiple of the slice width."""
     rng = np.random.default_rng(n)
     lens = np.concatenate([rng.integers(0, 70, size=400), [900, 0, 300, 2100, 64, 33, 32, 1]])
     p = csr_from_row_lengths(lens, 700, n, seed=n + 1, duplicates=True)
-    for tune in ("sliced=1,pack=0", "sliced=1,pack=1", "sliced=1,pack=1,ch=128,bch=256,lw=8"):
+    for tune in ("sliced=1,pack=0", "sliced=1,pack=1", "sliced=1,pack=1,ch=128,bch=256,lw=8", "sliced=64",
+                 "sliced=64,ch=128,bch=256,lw=8", "sliced=128"):
         with tuning(tune):
             run_both(p, label=f"sliced n={n} [{tune}]")
             run_both(integer_valued(p, seed=n), exact=True, label=f"sliced n={n} int [{tune}]")
