@@ -92,6 +92,20 @@ template <int V> __device__ __forceinline__ typename Vec<V>::type apply_epilogue
     return v;
 }
 
+// The same with the lane's V bias values already in registers (loops that store many rows per wavefront read them once).
+template <int V> __device__ __forceinline__ typename Vec<V>::type apply_epilogue_reg(typename Vec<V>::type v, bool has_bias,
+                                                                                  typename Vec<V>::type bias, int act) {
+    if (has_bias) v += bias;
+    if (act == 1) {
+        if constexpr (V == 1) v = fmaxf(v, 0.f);
+        else {
+#pragma unroll
+            for (int i = 0; i < V; ++i) v[i] = fmaxf(v[i], 0.f);
+        }
+    }
+    return v;
+}
+
 template <bool NT> __device__ __forceinline__ int ld_idx(const int32_t *p) {
     if constexpr (NT) return __builtin_nontemporal_load(p);
     else return *p;

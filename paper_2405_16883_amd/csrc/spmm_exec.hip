@@ -345,6 +345,11 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     }
     lrp[lane] = rpv;
     if (lane == 0) lrp[nr] = rlast;
+    // the lane's bias values are the same for every row of the window: read once
+    const bool has_bias = a.bias != nullptr;
+    vec bias_r[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) bias_r[t] = (has_bias && colok[t]) ? vload<V, UA>(a.bias + coff[t]) : vzero<V>();
     wave_lds_sync();
     for (int ri = grp; ri < nr; ri += S) {
         const int q0 = lrp[ri], q1 = lrp[ri + 1];
@@ -355,7 +360,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         float *dst = a.C + (int64_t)(r0 + ri) * a.ldc;
 #pragma unroll
         for (int t = 0; t < T; ++t)
-            if (colok[t]) vstore<V, NTC, UA>(dst + coff[t], apply_epilogue<V>(acc[t], a.bias ? a.bias + coff[t] : nullptr, a.act));
+            if (colok[t]) vstore<V, NTC, UA>(dst + coff[t], apply_epilogue_reg<V>(acc[t], has_bias, bias_r[t], a.act));
     }
 }
 
