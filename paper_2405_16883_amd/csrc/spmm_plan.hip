@@ -391,7 +391,7 @@ static int32_t want_sliced(int32_t m, int32_t k, int64_t nnz, int32_t n, bool ho
     const bool long_rows = nnz / m >= 64 && b_bytes >= 8ll << 20;
     if (long_rows && slice_bytes <= kL2SliceBudget) return kSliceCols;
     if (hot_candidate) return 0;  // the hot/cold split needs whole rows
-    if (long_rows && slice_bytes <= 13ll << 20) return kSliceCols;
+    if (long_rows && slice_bytes <= 13ll << 20 && n >= 128) return kSliceCols;  // n = 64 with a 13 MB slice: 2-6 % more time
     // B of 6 MB (1.5 L2s), 410 entries per row, n = 384: 19 % less time with 256-byte slices; B of 4 MB: 23 % more
     return (n >= 128 && n % 64 == 0 && b_bytes >= 6ll << 20) ? 64 : 0;
 }
