@@ -55,7 +55,7 @@ typedef struct scorch_spmm_plan_s scorch_spmm_plan_t; /* small host-side handle 
 
 /*
  * Plan-free SpMM: C = A.B in natural row order.  A wavefront takes a short run of consecutive rows
- * (up to 4), walks the short ones (up to 32 entries) side by side and streams the longer ones; the
+ * (up to 4, up to 16 for small n), walks the short ones (up to 32 entries) side by side and streams the longer ones; the
  * four wavefronts of a workgroup work together on rows with more than 2048 entries (more than 256
  * where such rows are rare).  Always available and correct for any valid input; no load balancing
  * beyond that, so a row with very many entries still runs on a single workgroup.  (Definition: see

@@ -780,7 +780,9 @@ scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, cons
     a.n = n;
     // rows per wavefront: 4 once that leaves a workgroup for every compute unit (measured: 1, 2, 4, 8, 16 rows on the
     // five benchmark workloads; 4 is within 1 % of the best of each that has 16 384 rows or more)
-    a.rows_per_wave = (int32_t)std::min<int64_t>(4, std::max<int64_t>(1, m / 4096));
+    // (narrow lane groups, i.e. many groups per wavefront: up to one row per group)
+    const int64_t rows_cap = std::max(4, std::min(kNaturalRowsMax, kWave / mp.G));
+    a.rows_per_wave = (int32_t)std::min<int64_t>(rows_cap, std::max<int64_t>(1, m / 4096));
     a.nb_wave = (int32_t)ceil_div64(m, (int64_t)kWavesPerBlock * a.rows_per_wave);
     a.ncoltiles = mp.ncoltiles;
     const int64_t grid = (int64_t)a.nb_wave * mp.ncoltiles;

@@ -188,14 +188,15 @@ def test_edge_shapes(name):
         run_both(integer_valued(p, seed=12), exact=True, label=f"{name} n={n} k={k} int")
 
 
-@pytest.mark.parametrize("n", [1, 33, 128, 300])
-def test_plan_free_row_runs(n):
-    """With 16 384 rows or more the plan-free kernel gives a wavefront a run of 4 consecutive rows: short rows are staged
+@pytest.mark.parametrize("m,n", [(16384 + 37, 1), (16384 + 37, 33), (16384 + 37, 128), (16384 + 37, 300),
+                                 (65536 + 5, 1), (65536 + 5, 8), (65536 + 5, 24)])
+def test_plan_free_row_runs(m, n):
+    """With 16 384 rows or more the plan-free kernel gives a wavefront a run of 4 consecutive rows (up to 16 with 65 536
+    rows or more and narrow lane groups, i.e. small n): short rows are staged
     together (at most 320 entries, rows of up to 32), longer ones streamed, rows beyond 256 / 2 048 entries left to
     the whole workgroup depending on how many of them the workgroup has.  Row lengths sit on every one of these limits,
     in runs that mix them, in a matrix whose last workgroup is ragged."""
     rng = np.random.default_rng(21)
-    m = 16384 + 37
     lens = rng.integers(0, 41, size=m)
     special = [0, 1, 31, 32, 33, 64, 255, 256, 257, 287, 288, 289, 319, 320, 321, 2047, 2048, 2049, 3000]
     for i, pos in enumerate(range(5, m - 64, 211)):
