@@ -457,7 +457,9 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     if (t.alpha > 0) p.ALPHA = t.alpha;
     if (t.lw > 0) p.LW = t.lw;
     if (t.ch > 0) p.CH = t.ch;
-    p.BCH = 4 * p.CH;
+    // One-lane groups (n <= 4): a workgroup takes 256 entries per step, so much longer pieces are still short chains,
+    // and rows that are not cut need no second launch (mid-size graph pattern, n = 1: 21.2 -> 18.1 us).
+    p.BCH = (n <= 4 ? 64 : 4) * p.CH;
     if (t.bch > 0) p.BCH = t.bch;
     if (t.u > 0) p.U = t.u;
     if (t.nt >= 0) p.NT = t.nt;
