@@ -172,6 +172,17 @@ def time_widenings(res, torch, sp, steps=30, warmup=5):
     ms_u = _event_ms(torch, unfused, steps, warmup)
     out["epilogue"] = {"fused_event_ms_mean": ms_e, "plain_spmm_event_ms_mean": ms_p,
                        "spmm_then_elementwise_event_ms_mean": ms_u}
+    # one graph-convolution layer relu(A (H W) + b), hidden width n -> n (square patterns only): dense product in the
+    # dense library, aggregation + bias + activation in one planned call
+    if p.m == p.k:
+        from paper_2405_16883_amd.gcn import GcnLayer
+        layer = GcnLayer(p.m, res.rowptr, res.colidx, res.vals, p.nnz)
+        H = torch.randn((p.m, p.n), generator=g, dtype=torch.float32, device=dev)
+        W = torch.randn((p.n, p.n), generator=g, dtype=torch.float32, device=dev) * 0.05
+        ms_l = _event_ms(torch, lambda: layer.forward(H, W, bias, relu=True), steps, warmup)
+        ms_mm = _event_ms(torch, lambda: torch.mm(H, W), steps, warmup)
+        layer.close()
+        out["gcn_layer"] = {"width": int(p.n), "event_ms_mean": ms_l, "dense_product_event_ms_mean": ms_mm}
     # second storage formats: row pointers from sorted row coordinates / from the list of stored rows
     rows = torch.repeat_interleave(torch.arange(p.m, dtype=torch.int32, device=dev),
                                    (res.rowptr[1:] - res.rowptr[:-1]).long())
@@ -382,7 +393,8 @@ def main():
                 log(f"[bench] on cfg 3 pattern: spmv {w['spmv']['event_ms_mean'] * 1e3:.1f} us ({100 * w['spmv']['frac_hbm']:.1f}% of HBM peak); "
                     f"spmm+bias+relu fused {w['epilogue']['fused_event_ms_mean'] * 1e3:.1f} us, plain spmm "
                     f"{w['epilogue']['plain_spmm_event_ms_mean'] * 1e3:.1f} us, spmm then elementwise "
-                    f"{w['epilogue']['spmm_then_elementwise_event_ms_mean'] * 1e3:.1f} us; rowptr from coo "
+                    f"{w['epilogue']['spmm_then_elementwise_event_ms_mean'] * 1e3:.1f} us; GCN layer (width {w['gcn_layer']['width']}) "
+                    f"{w['gcn_layer']['event_ms_mean'] * 1e3:.1f} us of which dense product {w['gcn_layer']['dense_product_event_ms_mean'] * 1e3:.1f} us; rowptr from coo "
                     f"{w['formats']['coo_rowptr_event_ms_mean'] * 1e3:.1f} us (ok {w['formats']['coo_matches_rowptr']}), from dcsr "
                     f"{w['formats']['dcsr_rowptr_event_ms_mean'] * 1e3:.1f} us (ok {w['formats']['dcsr_matches_rowptr']})")
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
