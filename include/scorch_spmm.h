@@ -98,7 +98,8 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * reads only those rows of B with the default cache policy and the others with the streaming policy.
  * This changes no result bit.
  * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>"
- * overrides the built-in parameter choice (for experiments).
+ * overrides the built-in parameter choice (for experiments; sliced = 0, 1 (= 32), 32, 64 or 128 columns of B per
+ * accelerator-die slice, panel = 0, 1 or 2).
  */
 scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
                                  const int32_t *rowptr, const int32_t *colidx,
