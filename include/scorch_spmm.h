@@ -181,7 +181,8 @@ scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spm
  * of Ct.  d must not exceed 1024 (any alignment of B and Ct); larger d gives SCORCH_ERR_UNSUPPORTED.  out_vals (float[nnz], device) may be the same array as vals
  * (in place) and must otherwise not overlap any input.  fp32 products, fp32 accumulation, fixed
  * summation order.  The planned variant reuses a plan made by scorch_spmm_plan for the same rowptr
- * (any n); the plan-free variant runs one wavefront per row.
+ * (any n); the plan-free variant walks the rows in natural order like scorch_spmm_csr (short runs
+ * of rows per wavefront, very long rows shared by the four wavefronts of a workgroup).
  */
 scorch_status_t scorch_sddmm_csr(int32_t m, int32_t k, int32_t d,
                                  const int32_t *rowptr, const int32_t *colidx, const float *vals,

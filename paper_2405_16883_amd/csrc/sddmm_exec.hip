@@ -16,6 +16,8 @@
 #include "device_util.h"
 #include "spmm_internal.h"
 
+#include <algorithm>
+
 namespace scorch {
 
 constexpr int kSddmmBatch = 8;
@@ -35,7 +37,15 @@ struct SddmmArgs {
     int32_t n_windows, n_wave_rows, n_items;
     int32_t nb_items, nb_wave, nb_win;
     int32_t LW;
+    int32_t rows_per_wave;  // plan-free path only: consecutive rows taken by one wavefront
 };
+
+// Plan-free path: row lengths up to which a lane group walks a row alone / a wavefront streams a row alone (the larger
+// limit when the workgroup has more than two rows beyond the smaller one), and the longest run of rows per wavefront.
+constexpr int kSddmmShort = 32;
+constexpr int kSddmmMid = 256;
+constexpr int kSddmmLong = 2048;
+constexpr int kSddmmRowsMax = 16;
 
 // Sums r[0..7] over the G lanes of a group.  Returns, in every lane, the total of entry
 // u = 4*bit0(lig) + 2*bit1(lig) + bit2(lig) of the batch.
@@ -182,12 +192,72 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
     const uint32_t b = blockIdx.x;
 
     if constexpr (!PLANNED) {
-        // plan-free: one wavefront per row in natural order
-        const int64_t row = (int64_t)b * kWavesPerBlock + wv;
-        if (row >= a.m) return;
-        load_x<V, T, UA>(x, a.B + row * a.ldb, colok, coff, nmask);
-        sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok,
-                                      coff, nmask);
+        // Plan-free: rows in natural order, a run of consecutive rows per wavefront.  The wavefront reads the run's row
+        // pointers once and proceeds greedily: the next rows that are short and fit the LDS stage together are staged
+        // and walked one row per lane group; a longer row is streamed by the whole wavefront; a row beyond kSddmmLong
+        // entries (kSddmmMid when such rows are rare in the workgroup, i.e. the outliers of a graph) is left to the
+        // end, where the 4 wavefronts split its entries (entries are independent: nothing to combine).
+        __shared__ int s_long[kWavesPerBlock * kSddmmRowsMax];
+        __shared__ int s_nlong, s_nmid;
+        const int NR = a.rows_per_wave;
+        const int64_t r0 = ((int64_t)b * kWavesPerBlock + wv) * NR;
+        const int nr = (int)max((int64_t)0, min((int64_t)NR, (int64_t)a.m - r0));
+        if (tid == 0) {
+            s_nlong = 0;
+            s_nmid = 0;
+        }
+        __syncthreads();
+        const int rpv = nr > 0 ? a.rowptr[r0 + min(lane, nr)] : 0;
+        const int rnext = __shfl_down(rpv, 1, kWave);  // lanes past the run hold the last pointer; lane 63 is never a row
+        const int nmid = (int)__builtin_popcountll(__ballot(lane < nr && rnext - rpv > kSddmmMid));
+        if (lane == 0 && nmid > 0) atomicAdd(&s_nmid, nmid);
+        __syncthreads();
+        const int long_limit = s_nmid <= 2 ? kSddmmMid : kSddmmLong;
+        if (nr > 0) {
+            lrp[lane] = rpv;
+            wave_lds_sync();
+            int i = 0;
+            while (i < nr) {
+                const int base = lrp[i];
+                // rows i .. j-1: the longest run of short rows that fits the stage
+                const bool stops = lane >= i && (lane >= nr || rnext - rpv > kSddmmShort || rnext - base > kStageMax);
+                const int j = __builtin_ctzll(__ballot(stops));  // lane nr always stops
+                if (j == i) {
+                    const int p1 = lrp[i + 1];
+                    if (p1 - base <= long_limit) {
+                        load_x<V, T, UA>(x, a.B + (r0 + i) * a.ldb, colok, coff, nmask);
+                        sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, base, p1, kWave, a, Yc, colok, coff, nmask);
+                    } else if (lane == 0) {
+                        s_long[atomicAdd(&s_nlong, 1)] = (int)(r0 + i);
+                    }
+                    ++i;
+                    continue;
+                }
+                const int cnt = min(lrp[j] - base, kStageMax);
+                for (int e = lane; e < cnt; e += kWave) {
+                    lcol[e] = a.colidx[base + e];
+                    lval[e] = a.vals[base + e];
+                }
+                wave_lds_sync();
+                for (int ri = i + grp; ri < j; ri += S) {
+                    const int q0 = lrp[ri], q1 = lrp[ri + 1];
+                    if (q1 == q0) continue;
+                    load_x<V, T, UA>(x, a.B + (r0 + ri) * a.ldb, colok, coff, nmask);
+                    sddmm_entries<V, G, T, UA>(x, lcol, lval, q0 - base, q1 - base, 1, Yc, a.ldct, colok, coff, nmask, lig,
+                                               a.out + base);
+                }
+                wave_lds_sync();  // the stage is refilled next
+                i = j;
+            }
+        }
+        __syncthreads();
+        const int nlong = s_nlong;
+        for (int w = 0; w < nlong; ++w) {
+            const int64_t row = s_long[w];
+            load_x<V, T, UA>(x, a.B + row * a.ldb, colok, coff, nmask);
+            sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, a.rowptr[row] + wv * kWave, a.rowptr[row + 1], kBlock,
+                                          a, Yc, colok, coff, nmask);
+        }
         return;
     }
 
@@ -326,7 +396,11 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
         grid = (int64_t)a.nb_items + a.nb_wave + a.nb_win;
         fn = pick_sddmm<true>(V, G, T, UA);
     } else {
-        grid = ((int64_t)m + kWavesPerBlock - 1) / kWavesPerBlock;
+        // rows per wavefront: 4 (up to one per lane group, 16 at most, when the groups are narrow) once that leaves a
+        // workgroup for every compute unit
+        const int64_t rows_cap = std::max(4, std::min(kSddmmRowsMax, kWave / G));
+        a.rows_per_wave = (int32_t)std::min<int64_t>(rows_cap, std::max<int64_t>(1, m / 4096));
+        grid = ((int64_t)m + (int64_t)kWavesPerBlock * a.rows_per_wave - 1) / ((int64_t)kWavesPerBlock * a.rows_per_wave);
         fn = pick_sddmm<false>(V, G, T, UA);
     }
     if (grid > 0x7fffffffLL) {

@@ -146,3 +146,23 @@ def test_sddmm_random_small_problems(block):
             run_and_check(integer_valued(p, seed=i), d, i + 1, integer=True, ldb=ldb, ldct=ldct, label=label + " int")
             run_and_check(integer_valued(p, seed=i), d, i + 2, integer=True, ldb=ldb, ldct=ldct, planned=False,
                           label=label + " int plan-free")
+
+
+@pytest.mark.parametrize("m,d", [(16384 + 37, 128), (16384 + 37, 300), (16384 + 37, 33), (65536 + 5, 8), (65536 + 5, 32)])
+def test_sddmm_plan_free_row_runs(m, d):
+    """The plan-free kernel gives a wavefront a run of consecutive rows (4 with 16 384 rows or more, up to 16 with
+    65 536 rows or more and narrow lane groups): row lengths sit on every staging and long-row limit, in runs that mix
+    them, in a matrix whose last workgroup is ragged."""
+    rng = np.random.default_rng(31)
+    lens = rng.integers(0, 41, size=m)
+    special = [0, 1, 31, 32, 33, 64, 255, 256, 257, 287, 288, 289, 319, 320, 321, 2047, 2048, 2049, 3000]
+    for i, pos in enumerate(range(5, m - 64, 211)):
+        lens[pos] = special[i % len(special)]
+    lens[1000:1016] = 20
+    lens[2000:2004] = [80, 80, 80, 80]
+    lens[3000:3016] = 300  # a workgroup with many rows beyond 256 entries: every wavefront keeps its own
+    lens[4000:4016] = [0] * 15 + [257]  # a single such row in a workgroup: shared by the 4 wavefronts
+    lens[m - 3:] = [2049, 0, 33]
+    p = csr_from_row_lengths(lens.tolist(), 5000, 4, seed=32, duplicates=True, sorted_cols=False)
+    run_and_check(p, d, 5, planned=False, label=f"plan-free row runs m={m} d={d}")
+    run_and_check(integer_valued(p, seed=33), d, 6, integer=True, planned=False, label=f"plan-free row runs int m={m} d={d}")
