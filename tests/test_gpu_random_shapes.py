@@ -55,3 +55,34 @@ def test_random_small_problems(block):
                 check_against_oracle(q, d.run_planned(plan), d.ldc, exact=exact, label=label + " planned")
                 check_against_oracle(q, d.run_natural(), d.ldc, exact=exact, label=label + " plan-free")
                 plan.destroy()
+
+
+def draw_tall_case(i):
+    """Matrices tall enough that the plan-free kernels give a wavefront a run of several rows, and wide enough
+    that the planner's column slicing applies to some of them."""
+    rng = np.random.default_rng(5000 + i)
+    m = int(rng.choice([8192, 12000, 16385, 40000, 70001]))
+    k = int(rng.choice([64, 1000, 20000]))
+    n = int(rng.choice([1, 4, 8, 24, 64, 100, 128, 192, 256]))
+    kind = int(rng.integers(0, 3))
+    if kind == 0:
+        lens = rng.integers(0, 40, size=m)
+    elif kind == 1:
+        lens = np.minimum((rng.pareto(1.1, size=m) * 4).astype(np.int64), 6000)  # heavy tail: outlier rows
+    else:
+        lens = rng.choice([0, 1, 30, 33, 250, 260, 300], size=m, p=[0.3, 0.3, 0.2, 0.1, 0.04, 0.03, 0.03])
+    p = csr_from_row_lengths(lens, k, n, seed=i, duplicates=True, sorted_cols=bool(rng.integers(0, 2)))
+    return p
+
+
+@pytest.mark.parametrize("i", range(8))
+def test_random_tall_problems(i):
+    p = draw_tall_case(i)
+    label = f"tall case {i}: m={p.m} k={p.k} n={p.n} nnz={p.nnz}"
+    print(label, flush=True)
+    for q, exact in ((p, False), (integer_valued(p, seed=i), True)):
+        d = DeviceProblem(q)
+        plan = d.make_plan()
+        check_against_oracle(q, d.run_planned(plan), d.ldc, exact=exact, label=label + " planned")
+        check_against_oracle(q, d.run_natural(), d.ldc, exact=exact, label=label + " plan-free")
+        plan.destroy()
