@@ -97,9 +97,10 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * each column occurs and marks the most referenced columns (up to 64 MB of rows of B) as hot; execution then
  * reads only those rows of B with the default cache policy and the others with the streaming policy.
  * This changes no result bit.
- * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>"
+ * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>,sdblk=.."
  * overrides the built-in parameter choice (for experiments; sliced = 0, 1 (= 32), 32, 64 or 128 columns of B per
- * accelerator-die slice, panel = 0, 1 or 2).
+ * accelerator-die slice, panel = 0, 1 or 2; sdblk = blocks of columns of A per accelerator die in the planned
+ * SDDMM, 0 = row-wise kernel, read at every SDDMM call).
  */
 scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
                                  const int32_t *rowptr, const int32_t *colidx,

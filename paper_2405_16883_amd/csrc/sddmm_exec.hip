@@ -38,6 +38,9 @@ struct SddmmArgs {
     int32_t nb_items, nb_wave, nb_win;
     int32_t LW;
     int32_t rows_per_wave;  // plan-free path only: consecutive rows taken by one wavefront
+    int32_t k;              // column-block kernel: rows of Ct
+    int32_t block_rows;     // column-block kernel: rows of Ct per block
+    int32_t rounds;         // column-block kernel: blocks per XCD (block = round * 8 + XCD)
 };
 
 // Plan-free path: row lengths up to which a lane group walks a row alone / a wavefront streams a row alone (the larger
@@ -84,11 +87,12 @@ template <int V> __device__ __forceinline__ void zero_head(typename Vec<V>::type
 
 // One lane group computes the staged entries e0, e0+es, ... (< e_end) of a row whose B row is in x:
 //   out_base[e] = val[e] * <x, Ct[col[e], :]>
+// With lidx, staged entry e is written to out_base[lidx[e]] (entries picked out of a row, see the column-block kernel).
 template <int V, int G, int T, bool UA>
 __device__ __forceinline__ void sddmm_entries(const typename Vec<V>::type (&x)[T], const int *lcol, const float *lval,
                                               int e0, int e_end, int es, const float *Yc, int64_t ldct,
                                               const bool (&colok)[T], const int (&coff)[T], const int (&nmask)[T],
-                                              int lig, float *out_base) {
+                                              int lig, float *out_base, const int *lidx = nullptr) {
     using vec = typename Vec<V>::type;
     const int my_u = ((lig & 1) << 2) | (lig & 2) | ((lig & 4) >> 2);
     for (int e = e0; e < e_end; e += es * kSddmmBatch) {
@@ -120,7 +124,7 @@ __device__ __forceinline__ void sddmm_entries(const typename Vec<V>::type (&x)[T
         }
         const float total = group_reduce8<G>(r, lig);
         const int ee = e + my_u * es;
-        if (lig < kSddmmBatch && ee < e_end) out_base[ee] = lval[ee] * total;
+        if (lig < kSddmmBatch && ee < e_end) out_base[lidx ? lidx[ee] : ee] = lval[ee] * total;
     }
 }
 
@@ -312,6 +316,82 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
     }
 }
 
+// Column-block kernel, for matrices whose rows are long and whose second factor overflows an XCD's L2 a few times:
+// the rows of Ct (= columns of A) are cut into 8 * rounds blocks, and XCD x takes, for every row of A, only the stored
+// entries whose column falls into block round * 8 + x.  Its gathers then stay within a block of Ct that its L2 keeps.
+// Entries of an SDDMM are independent, so nothing has to be combined between XCDs (the SpMM cannot do this: it would
+// have to add partial rows).  A wavefront scans the row's colidx 64 at a time, compacts the entries of its block into
+// the LDS stage together with their positions, and the lane groups then take the staged entries in turn.  Every XCD
+// scans every row: 8 * rounds reads of colidx and of the rows of B, against 4 d bytes gathered per entry.
+constexpr int kSddmmBlockRowsPerWave = 4;
+
+template <int V, int G, int T, bool UA>
+__global__ __launch_bounds__(kBlock) void sddmm_colblock_kernel(const SddmmArgs a) {
+    using vec = typename Vec<V>::type;
+    constexpr int S = kWave / G;
+    constexpr int GV = G * V;
+    __shared__ int s_raw[kWavesPerBlock * 3 * kStageMax];
+    const int tid = threadIdx.x;
+    const int wv = tid >> 6;
+    const int lane = tid & 63;
+    const int grp = lane / G;
+    const int lig = lane % G;
+    const int c0 = lig * V;
+    bool colok[T];
+    int coff[T], nmask[T];
+#pragma unroll
+    for (int t = 0; t < T; ++t) {
+        colok[t] = (c0 + t * GV) < a.d;
+        coff[t] = UA ? min(c0 + t * GV, a.d - V) : c0 + t * GV;
+        nmask[t] = c0 + t * GV - coff[t];
+    }
+    int *lcol = s_raw + wv * 3 * kStageMax;
+    float *lval = reinterpret_cast<float *>(lcol + kStageMax);
+    int *lidx = lcol + 2 * kStageMax;
+    // workgroup index = (round * row groups + row group) * 8 + XCD: consecutive workgroups go to different XCDs
+    const uint32_t xcd = blockIdx.x & (kXcds - 1);
+    const uint32_t q = blockIdx.x / kXcds;
+    const uint32_t row_groups = (uint32_t)((a.m + kWavesPerBlock * kSddmmBlockRowsPerWave - 1) / (kWavesPerBlock * kSddmmBlockRowsPerWave));
+    const uint32_t round = q / row_groups;
+    const uint32_t rg = q - round * row_groups;
+    const int64_t lo64 = (int64_t)(round * kXcds + xcd) * a.block_rows;
+    if (lo64 >= a.k) return;
+    const int lo = (int)lo64;
+    const int hi = (int)min((int64_t)a.k, lo64 + a.block_rows);
+    const int64_t row0 = ((int64_t)rg * kWavesPerBlock + wv) * kSddmmBlockRowsPerWave;
+    vec x[T];
+    for (int64_t row = row0; row < min((int64_t)a.m, row0 + kSddmmBlockRowsPerWave); ++row) {
+        const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
+        bool have_x = false;
+        int staged = 0;
+        for (int base = p0; base < p1; base += kWave) {
+            const int p = base + lane;
+            const int c = p < p1 ? a.colidx[p] : -1;
+            const bool in = c >= lo && c < hi;
+            const unsigned long long mask = __ballot(in);
+            if (mask != 0ull) {
+                const int pos = staged + (int)__builtin_popcountll(mask & ((1ull << lane) - 1ull));
+                if (in) {
+                    lcol[pos] = c;
+                    lval[pos] = a.vals[p];
+                    lidx[pos] = p;
+                }
+                staged += (int)__builtin_popcountll(mask);
+            }
+            if (staged > kStageMax - kWave || (base + kWave >= p1 && staged > 0)) {
+                if (!have_x) {
+                    load_x<V, T, UA>(x, a.B + row * a.ldb, colok, coff, nmask);
+                    have_x = true;
+                }
+                wave_lds_sync();
+                sddmm_entries<V, G, T, UA>(x, lcol, lval, grp, staged, S, a.Ct, a.ldct, colok, coff, nmask, lig, a.out, lidx);
+                wave_lds_sync();
+                staged = 0;
+            }
+        }
+    }
+}
+
 // ------------------------------------------------------------------------------------------
 typedef void (*sddmm_fn)(const SddmmArgs);
 
@@ -334,6 +414,26 @@ template <bool PLANNED> static sddmm_fn pick_sddmm(int V, int G, int T, bool UA)
     SCORCH_SD(1, 8, 1, false)
 #undef SCORCH_SD_G4
 #undef SCORCH_SD
+}
+
+static sddmm_fn pick_sddmm_colblock(int V, int G, int T, bool UA) {
+#define SCORCH_SDB(Vv, Gg, Tt, Uu) return sddmm_colblock_kernel<Vv, Gg, Tt, Uu>;
+#define SCORCH_SDB_G4(Uu)                                 \
+    if (T == 4) { SCORCH_SDB(4, 64, 4, Uu) }              \
+    if (T == 2) { SCORCH_SDB(4, 64, 2, Uu) }              \
+    switch (G) {                                          \
+        case 8: SCORCH_SDB(4, 8, 1, Uu)                   \
+        case 16: SCORCH_SDB(4, 16, 1, Uu)                 \
+        case 32: SCORCH_SDB(4, 32, 1, Uu)                 \
+        default: SCORCH_SDB(4, 64, 1, Uu)                 \
+    }
+    if (V == 4) {
+        if (UA) { SCORCH_SDB_G4(true) } else { SCORCH_SDB_G4(false) }
+    }
+    if (V == 2) { SCORCH_SDB(2, 8, 1, false) }
+    SCORCH_SDB(1, 8, 1, false)
+#undef SCORCH_SDB_G4
+#undef SCORCH_SDB
 }
 
 static bool pick_sddmm_mapping(int32_t d, const float *B, int64_t ldb, const float *Ct, int64_t ldct, int &V, int &G,
@@ -381,7 +481,29 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
     a.d = d;
     int64_t grid;
     sddmm_fn fn;
-    if (plan) {
+    // Column blocks over the XCDs (sddmm_colblock_kernel): rows without outliers (none cut by the plan) and a second
+    // factor of a few L2s.  Measured against the row-wise kernel on uniform and pruned patterns, k = 4096 ... 65 536,
+    // d = 64 ... 512: Ct of 17-34 MB: 1.3-2.2x faster with one block per XCD (also with 33 entries per row); 67 MB:
+    // 2.0-2.2x with two blocks per XCD (one: 1.5x); 8 MB: between 1.27x faster (1638 entries per row) and 1.15x slower
+    // (164); 4 MB and less: 1.1-3x slower.  sdblk=<blocks per XCD> in the tuning variable forces it, sdblk=0 turns it off.
+    int32_t rounds = 0;
+    if (plan && plan->m > 0 && plan->k > 0) {
+        const int64_t ct_bytes = (int64_t)plan->k * d * 4;
+        const int64_t avg = plan->nnz / plan->m;
+        const bool big_enough = (avg >= 1024 && ct_bytes >= (8ll << 20)) || (avg >= 64 && ct_bytes >= (12ll << 20)) ||
+                                (avg >= 24 && ct_bytes >= (16ll << 20));
+        if (big_enough && plan->n_split == 0 && ct_bytes <= (84ll << 20)) rounds = ct_bytes <= (42ll << 20) ? 1 : 2;
+        const Tuning t = read_tuning_from_env();
+        if (t.sdblk >= 0) rounds = std::min(t.sdblk, 64);
+    }
+    if (rounds > 0) {
+        a.k = plan->k;
+        a.rounds = rounds;
+        a.block_rows = (int32_t)(((int64_t)plan->k + (int64_t)kXcds * rounds - 1) / ((int64_t)kXcds * rounds));
+        const int64_t row_groups = ((int64_t)m + kWavesPerBlock * kSddmmBlockRowsPerWave - 1) / (kWavesPerBlock * kSddmmBlockRowsPerWave);
+        grid = row_groups * kXcds * rounds;
+        fn = pick_sddmm_colblock(V, G, T, UA);
+    } else if (plan) {
         char *ws = plan->workspace;
         a.win_row_start = reinterpret_cast<const int32_t *>(ws + plan->layout.off_win);
         a.wave_rows = reinterpret_cast<const int32_t *>(ws + plan->layout.off_wave);

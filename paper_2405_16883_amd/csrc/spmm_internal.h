@@ -41,7 +41,8 @@ struct PlanParams {
 };
 
 struct Tuning {
-    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1, panel = -1, hot = -1;
+    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1, panel = -1, hot = -1,
+            sdblk = -1;
 };
 Tuning read_tuning_from_env();
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t);

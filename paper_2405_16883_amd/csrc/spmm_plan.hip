@@ -362,6 +362,7 @@ Tuning read_tuning_from_env() {
         else if (!std::strcmp(tok, "pack")) t.pack = v;
         else if (!std::strcmp(tok, "panel")) t.panel = v;
         else if (!std::strcmp(tok, "hot")) t.hot = v;
+        else if (!std::strcmp(tok, "sdblk")) t.sdblk = v;
     }
     return t;
 }

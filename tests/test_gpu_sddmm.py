@@ -59,7 +59,8 @@ def run_and_check(p, d, seed, integer=False, ldb=None, ldct=None, label="", plan
         assert not bad.any(), f"{label}: {int(bad.sum())} entries out of tolerance, worst {np.nanmax(err / bound):.3g} at {np.nonzero(bad)[0][:4]}"
 
 
-TUNES = [None, "bn=64,alpha=2,lw=8,ch=32,bch=64", "bn=256,lw=64,ch=256,bch=256", "bn=128,lw=0,ch=64,bch=128"]
+TUNES = [None, "bn=64,alpha=2,lw=8,ch=32,bch=64", "bn=256,lw=64,ch=256,bch=256", "bn=128,lw=0,ch=64,bch=128",
+         "sdblk=1", "sdblk=3"]  # sdblk: entries dealt to the XCDs by column block (1 or 3 blocks per XCD)
 
 
 @pytest.mark.parametrize("tune", TUNES)
@@ -82,6 +83,9 @@ def test_sddmm_inner_dimensions(d):
         run_and_check(p, d, d, label=f"d={d}")
         run_and_check(integer_valued(p, seed=d), d, d + 1, integer=True, label=f"d={d} int")
         run_and_check(integer_valued(p, seed=d), d, d + 2, integer=True, planned=False, label=f"d={d} int plan-free")
+    with tuning("sdblk=2"):  # column blocks over the XCDs
+        run_and_check(p, d, d, label=f"d={d} column blocks")
+        run_and_check(integer_valued(p, seed=d), d, d + 1, integer=True, label=f"d={d} int column blocks")
 
 
 @pytest.mark.parametrize("d,ldb,ldct", [(64, 72, 68), (100, 101, 103), (7, 9, 8), (128, 132, 136), (256, 260, 256), (300, 301, 303),
@@ -98,6 +102,9 @@ def test_sddmm_edge_patterns_and_in_place():
         run_and_check(p, 64, 9, integer=True, label=f"lens={lens[:3]}..")
         run_and_check(p, 64, 9, integer=True, planned=False, label=f"lens={lens[:3]}.. plan-free")
         run_and_check(p, 64, 9, integer=True, in_place=True, label=f"lens={lens[:3]}.. in place")
+        with tuning("sdblk=1"):
+            run_and_check(p, 64, 9, integer=True, label=f"lens={lens[:3]}.. column blocks")
+            run_and_check(p, 64, 9, integer=True, in_place=True, label=f"lens={lens[:3]}.. column blocks in place")
 
 
 def test_sddmm_argument_errors():
