@@ -384,6 +384,10 @@ def main():
             if cfg == 1:
                 o["graph_replay_ms_per_step"] = time_graph_replay(r, torch, sp)
                 log(f"[bench] cfg 1 recorded into a HIP graph (20 steps per replay): {o['graph_replay_ms_per_step'] * 1e3:.2f} us per step")
+            if cfg == 2:
+                o["sddmm"] = time_sddmm(r, torch, sp, 256)
+                log(f"[bench] sddmm on cfg 2 pattern, d=256 (column blocks over the XCDs): {o['sddmm']['event_ms_mean']:.4f} ms  "
+                    f"{o['sddmm']['gflops']:.0f} GFLOP/s  {100 * o['sddmm']['frac_hbm']:.1f}% of HBM peak (min-traffic model)")
             if cfg == 3:
                 o["sddmm"] = time_sddmm(r, torch, sp, 128)
                 log(f"[bench] sddmm on cfg 3 pattern, d=128: {o['sddmm']['event_ms_mean']:.4f} ms  {o['sddmm']['gflops']:.0f} GFLOP/s  "
