@@ -125,6 +125,14 @@ def test_sddmm_full_size_gcn_graph():
     run_and_check(integer_valued(p, seed=5), 128, 12, integer=True, label="workload 3 pattern int")
 
 
+def test_sddmm_full_size_uniform_pattern_uses_column_blocks():
+    """Workload 2's pattern with d = 256: the second factor is 17 MB, rows have 164 entries, so the planned call deals
+    the entries to the XCDs by column block (its default there); every entry against the oracle."""
+    p = make_config(2, seed=0)
+    run_and_check(p, 256, 13, label="workload 2 pattern, d=256")
+    run_and_check(integer_valued(p, seed=6), 256, 14, integer=True, label="workload 2 pattern int, d=256")
+
+
 @pytest.mark.parametrize("block", range(6))
 def test_sddmm_random_small_problems(block):
     """Seeded random shapes, row-length mixes, leading dimensions and forced plan parameters."""
