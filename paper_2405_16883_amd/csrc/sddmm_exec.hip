@@ -483,8 +483,8 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
     sddmm_fn fn;
     // Column blocks over the XCDs (sddmm_colblock_kernel): rows without outliers (none cut by the plan) and a second
     // factor of a few L2s.  Measured against the row-wise kernel on uniform and pruned patterns, k = 4096 ... 65 536,
-    // d = 64 ... 512: Ct of 17-34 MB: 1.3-2.2x faster with one block per XCD (also with 33 entries per row); 67 MB:
-    // 2.0-2.2x with two blocks per XCD (one: 1.5x); 8 MB: between 1.27x faster (1638 entries per row) and 1.15x slower
+    // d = 64 ... 1024: Ct of 17-34 MB: 1.3-2.2x faster with one block per XCD (also with 33 entries per row); 67 MB:
+    // 1.4-2.2x with two blocks per XCD (one: 1.5x); 8 MB: between 1.27x faster (1638 entries per row) and 1.15x slower
     // (164); 4 MB and less: 1.1-3x slower.  sdblk=<blocks per XCD> in the tuning variable forces it, sdblk=0 turns it off.
     int32_t rounds = 0;
     if (plan && plan->m > 0 && plan->k > 0) {
@@ -492,7 +492,10 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
         const int64_t avg = plan->nnz / plan->m;
         const bool big_enough = (avg >= 1024 && ct_bytes >= (8ll << 20)) || (avg >= 64 && ct_bytes >= (12ll << 20)) ||
                                 (avg >= 24 && ct_bytes >= (16ll << 20));
-        if (big_enough && plan->n_split == 0 && ct_bytes <= (84ll << 20)) rounds = ct_bytes <= (42ll << 20) ? 1 : 2;
+        // one block per XCD and 42 MB of Ct, four at most (Ct of 134 MB: 1.3-1.8x faster with 3-4 blocks per XCD; 268 MB:
+        // 1.1-1.4x with 4)
+        if (big_enough && plan->n_split == 0 && ct_bytes <= (300ll << 20))
+            rounds = (int32_t)std::min<int64_t>(4, (ct_bytes + (42ll << 20) - 1) / (42ll << 20));
         const Tuning t = read_tuning_from_env();
         if (t.sdblk >= 0) rounds = std::min(t.sdblk, 64);
     }
