@@ -496,8 +496,7 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
         // 1.1-1.4x with 4)
         if (big_enough && plan->n_split == 0 && ct_bytes <= (300ll << 20))
             rounds = (int32_t)std::min<int64_t>(4, (ct_bytes + (42ll << 20) - 1) / (42ll << 20));
-        const Tuning t = read_tuning_from_env();
-        if (t.sdblk >= 0) rounds = std::min(t.sdblk, 64);
+        if (plan->tuning.sdblk >= 0) rounds = std::min(plan->tuning.sdblk, 64);  // as it stood when the plan was made
     }
     if (rounds > 0) {
         a.k = plan->k;

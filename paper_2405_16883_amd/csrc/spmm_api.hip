@@ -115,7 +115,8 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n, const int32_t 
     plan->k = k;
     plan->n = n;
     plan->nnz = nnz32;
-    plan->params = choose_params(m, k, nnz32, n, read_tuning_from_env());
+    plan->tuning = read_tuning_from_env();
+    plan->params = choose_params(m, k, nnz32, n, plan->tuning);
     plan->layout = layout_workspace(m, k, nnz32, n, plan->params);
     plan->workspace = static_cast<char *>(workspace);
     if (hipGetDevice(&plan->device) != hipSuccess) plan->device = -1;

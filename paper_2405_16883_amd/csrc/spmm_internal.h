@@ -6,6 +6,7 @@
 #include <stdint.h>
 
 #include "scorch_spmm.h"
+#include "tuning.h"
 #include "xcd_map.h"
 
 namespace scorch {
@@ -40,10 +41,7 @@ struct PlanParams {
     int32_t HOT;    // >0: budget in KB for the most referenced rows of B, which alone keep the default cache policy
 };
 
-struct Tuning {
-    int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1, panel = -1, hot = -1,
-            sdblk = -1;
-};
+// SCORCH_SPMM_TUNE, parsed (only scorch_spmm_plan and scorch_spmm_plan_workspace_bytes call this)
 Tuning read_tuning_from_env();
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t);
 
@@ -120,6 +118,7 @@ struct scorch_spmm_plan_s {
     int32_t m, k, n;
     int64_t nnz;
     int device;
+    scorch::Tuning tuning;  // the environment overrides as they stood when the plan was made
     scorch::PlanParams params;
     scorch::WorkspaceLayout layout;
     char *workspace;

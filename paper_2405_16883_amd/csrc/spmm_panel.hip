@@ -47,6 +47,16 @@ __device__ __forceinline__ void panel_fetch(const f4 *Bt, int k, int k0, f4 *sbu
     }
 }
 
+// Barrier that publishes a fetched panel.  The direct-to-LDS loads are counted by the issuing wavefront's vector-memory
+// counter, and a workgroup barrier by itself only orders the LDS instructions a wavefront has issued: without the
+// wait, wavefront A could pass the barrier while its chunk of the panel is still in flight and wavefront B would read
+// stale LDS.  So every wavefront first drains its own loads (vmcnt(0)), then joins the barrier.  The fetch was issued
+// before the previous panel's work, so the wait is normally already satisfied.
+__device__ __forceinline__ void panel_publish() {
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+}
+
 template <int RW, int kBatch, int Q>
 struct PanelRows {
     int pend[RW], wbase[RW], pos[RW], colreg[RW], colnext[RW];
@@ -170,12 +180,12 @@ __global__ __launch_bounds__(16 * kWave) void spmm_panel_kernel(const PanelArgs 
         for (int q = 0; q < Q; ++q) st.acc[r][q] = f4{0.f, 0.f, 0.f, 0.f};
     }
     for (int k0 = 0; k0 < a.k; k0 += 2 * kRows) {
-        __syncthreads();  // panel k0 has landed in s_b0; nobody reads s_b1 any more
+        panel_publish();  // panel k0 has landed in s_b0; nobody reads s_b1 any more
         const bool odd = k0 + kRows < a.k;
         if (odd) panel_fetch<Q, KR>(Bt, a.k, k0 + kRows, s_b1, wv, lane);
         panel_compute<RW, kBatch, Q, KR>(st, s_b0, k0, lane, a.colidx, a.vals);
         if (odd) {
-            __syncthreads();  // panel k0 + kRows has landed in s_b1; nobody reads s_b0 any more
+            panel_publish();  // panel k0 + kRows has landed in s_b1; nobody reads s_b0 any more
             if (k0 + 2 * kRows < a.k) panel_fetch<Q, KR>(Bt, a.k, k0 + 2 * kRows, s_b0, wv, lane);
             panel_compute<RW, kBatch, Q, KR>(st, s_b1, k0 + kRows, lane, a.colidx, a.vals);
         }

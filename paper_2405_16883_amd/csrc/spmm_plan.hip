@@ -12,10 +12,10 @@
 // All lists come out in ascending row order (stable compaction), so the plan is a pure function
 // of rowptr and the parameters.
 #include "spmm_internal.h"
+#include "rowptr_keys.h"
 
 #include <algorithm>
 #include <cstdlib>
-#include <cstring>
 
 namespace scorch {
 
@@ -315,13 +315,13 @@ __global__ __launch_bounds__(kBlock) void rowptr_from_keys_kernel(const int32_t 
     for (int64_t p = (int64_t)blockIdx.x * kBlock + threadIdx.x; p <= count; p += (int64_t)gridDim.x * kBlock) {
         const int prev = p > 0 ? keys[p - 1] : -1;
         const int cur = p < count ? keys[p] : m;
-        const bool order_ok = strictly_increasing ? (cur > prev || p == 0) : cur >= prev;
-        if (!order_ok || (p < count && (cur < 0 || cur >= m))) {
+        int32_t lo, hi;
+        if (!rowptr_fill_range(p, count, prev, cur, m, strictly_increasing, lo, hi)) {
             if (bad_flag) *bad_flag = 1;
             continue;
         }
         const int32_t value = pos ? pos[p] : (int32_t)p;
-        for (int r = prev + 1; r <= cur; ++r) rowptr[r] = value;
+        for (int r = lo; r <= hi; ++r) rowptr[r] = value;  // 0 <= lo, hi <= m
     }
 }
 
@@ -339,33 +339,7 @@ scorch_status_t launch_rowptr_from_keys(int32_t m, int64_t count, const int32_t 
 // ------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------
-Tuning read_tuning_from_env() {
-    Tuning t;
-    const char *s = std::getenv("SCORCH_SPMM_TUNE");
-    if (!s) return t;
-    char buf[256];
-    std::strncpy(buf, s, sizeof(buf) - 1);
-    buf[sizeof(buf) - 1] = 0;
-    for (char *tok = std::strtok(buf, ","); tok; tok = std::strtok(nullptr, ",")) {
-        char *eq = std::strchr(tok, '=');
-        if (!eq) continue;
-        *eq = 0;
-        const int v = std::atoi(eq + 1);
-        if (!std::strcmp(tok, "bn")) t.bn = v;
-        else if (!std::strcmp(tok, "alpha")) t.alpha = v;
-        else if (!std::strcmp(tok, "lw")) t.lw = v;
-        else if (!std::strcmp(tok, "ch")) t.ch = v;
-        else if (!std::strcmp(tok, "bch")) t.bch = v;
-        else if (!std::strcmp(tok, "u")) t.u = v;
-        else if (!std::strcmp(tok, "nt")) t.nt = v;
-        else if (!std::strcmp(tok, "sliced")) t.sliced = v;
-        else if (!std::strcmp(tok, "pack")) t.pack = v;
-        else if (!std::strcmp(tok, "panel")) t.panel = v;
-        else if (!std::strcmp(tok, "hot")) t.hot = v;
-        else if (!std::strcmp(tok, "sdblk")) t.sdblk = v;
-    }
-    return t;
-}
+Tuning read_tuning_from_env() { return parse_tuning(std::getenv("SCORCH_SPMM_TUNE")); }
 
 static int32_t pow2_floor(int64_t x) {
     int32_t p = 1;
@@ -535,7 +509,7 @@ scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, cons
     plan->n_hot = 0;
     plan->hot_share = 0.f;
     if (plan->params.HOT && colidx && plan->nnz > 0 && plan->k > 0) {
-        scorch_status_t st = mark_hot_columns(plan, colidx, read_tuning_from_env().hot > 0, stream);
+        scorch_status_t st = mark_hot_columns(plan, colidx, plan->tuning.hot > 0, stream);
         if (st != SCORCH_OK) return st;
     }
     if (plan->m > 0) {

@@ -93,6 +93,59 @@ def check_against_oracle(p, Cfull, ldc, *, exact=False, rows=None, label=""):
     return float(np.max(np.abs(C - C_ref) / (RTOL_T * T + ATOL))) if C.size else 0.0
 
 
+def host_cores():
+    """Worker threads for the chunked oracle: the CPU share of a one-GPU machine, never more than the affinity mask."""
+    return max(1, min(16, len(os.sched_getaffinity(0))))
+
+
+def check_every_row_chunked(p, outputs, *, exact=False, chunks_per_core=4):
+    """Every element of one or more GPU results (dict label -> m x >=n float32 array) against the fp64 oracle.
+
+    The oracle is the same serial loop as everywhere else; it is only called on contiguous blocks of rows, one block
+    per call, several calls at a time on the host cores (ctypes releases the interpreter lock), and each block's
+    C_ref and T are dropped after the comparison, so that the 2 x 8 bytes per element never exist for the whole matrix.
+    Blocks hold about the same number of stored entries.  Returns the worst err/bound ratio per label."""
+    from concurrent.futures import ThreadPoolExecutor
+
+    cores = host_cores()
+    rp = p.rowptr.astype(np.int64)
+    nblocks = max(1, min(p.m, cores * chunks_per_core))
+    cuts = np.searchsorted(rp, np.linspace(0, rp[-1], nblocks + 1)[1:-1], side="left")
+    edges = np.unique(np.concatenate([[0], cuts, [p.m]])).astype(np.int64)
+    for label, C in outputs.items():
+        assert C.shape[0] >= p.m and C.shape[1] >= p.n, f"{label}: result has the wrong shape {C.shape}"
+
+    def one(block):
+        lo, hi = int(edges[block]), int(edges[block + 1])
+        C_ref, T = spmm_csr_oracle(p.m, p.n, p.rowptr, p.colidx, p.vals, p.B, p.ldb, rows=np.arange(lo, hi, dtype=np.int64))
+        res = {}
+        for label, C in outputs.items():
+            got = C[lo:hi, :p.n].astype(np.float64)
+            if exact:
+                bad = got != C_ref
+                neg0 = bool(np.signbit(got[got == 0]).any())
+                res[label] = (int(bad.sum()), (lo + int(np.argwhere(bad)[0][0])) if bad.any() else -1, 0.0, neg0)
+            else:
+                err = np.abs(got - C_ref)
+                bound = RTOL_T * T + ATOL
+                bad = ~(err <= bound)
+                res[label] = (int(bad.sum()), (lo + int(np.argwhere(bad)[0][0])) if bad.any() else -1,
+                              float(np.max(err / bound)) if err.size else 0.0, False)
+        return res
+
+    with ThreadPoolExecutor(max_workers=cores) as pool:
+        parts = list(pool.map(one, range(len(edges) - 1)))
+    worst = {}
+    for label in outputs:
+        nbad = sum(r[label][0] for r in parts)
+        first = min([r[label][1] for r in parts if r[label][1] >= 0], default=-1)
+        worst[label] = max(r[label][2] for r in parts)
+        assert nbad == 0, (f"{label}: {nbad} elements " + ("differ from the exact integer result" if exact else
+                           f"out of tolerance (worst err/bound {worst[label]:.3g})") + f"; first bad row {first}")
+        assert not any(r[label][3] for r in parts), f"{label}: -0.0 where +0.0 is required"
+    return worst
+
+
 def read_plan_arrays(plan):
     """Copy the plan's lists out of the workspace (layout documented in the C header)."""
     info = plan.info()

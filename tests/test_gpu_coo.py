@@ -38,6 +38,32 @@ def test_unsorted_or_out_of_range_rows_raise_the_flag():
     assert device_rowptr(4, [0, 1, 1, 3])[1] == 0
 
 
+@pytest.mark.parametrize("rows", [[-5, 3], [-5, -5, 3], [0, -2, 3], [9, 9], [2, 1000000], [-2147483648, 0],
+                                  [2147483647, 2147483647], [3, -7]])
+def test_bad_row_ids_raise_the_flag_and_write_nothing_outside_rowptr(rows):
+    """A key outside [0, m) must not steer the fill outside rowptr_out[0..m], whether it is the entry that closes a
+    range or its predecessor: rowptr_out sits in the middle of a guarded buffer."""
+    m, guard = 4, 4096
+    buf = torch.full((guard + m + 1 + guard,), -77, dtype=torch.int32, device=DEV)
+    out = buf[guard:guard + m + 1]
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    sp.scorch_coo_to_csr_rowptr(m, torch.tensor(rows, dtype=torch.int32, device=DEV), out, flag)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert int(flag.item()) == 1
+    assert np.all(host[:guard] == -77) and np.all(host[guard + m + 1:] == -77)
+    # the same through the doubly compressed entry point (strictly increasing ids)
+    buf.fill_(-77)
+    flag.zero_()
+    ids = torch.tensor(rows, dtype=torch.int32, device=DEV)
+    pos = torch.arange(len(rows) + 1, dtype=torch.int32, device=DEV)
+    sp.scorch_dcsr_to_csr_rowptr(m, ids, pos, out, flag)
+    torch.cuda.synchronize()
+    host = buf.cpu().numpy()
+    assert int(flag.item()) == 1
+    assert np.all(host[:guard] == -77) and np.all(host[guard + m + 1:] == -77)
+
+
 @pytest.mark.parametrize("cfg,scale", [(1, 1.0), (3, 0.08), (5, 0.06)])
 def test_spmm_from_a_coordinate_list(cfg, scale):
     p = make_scaled_config(cfg, scale, seed=5)
