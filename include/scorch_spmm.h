@@ -144,6 +144,28 @@ scorch_status_t scorch_spmm_csr_planned_epilogue(const scorch_spmm_plan_t *plan,
                                                  float *C, int32_t ldc,
                                                  void *stream);
 
+/*
+ * Planned SpMM for callers that cannot allocate device memory: code that may not call hipMalloc (tight serving
+ * loops, harnesses that forbid it) and therefore cannot hand scorch_spmm_plan a workspace.  Same operation, same
+ * arguments and same result bits as scorch_spmm_plan(m, k, n, rowptr, colidx, ...) followed by
+ * scorch_spmm_csr_planned on the same operands; the plan's row lists, partial rows and (for some shapes) repacked copy
+ * of B live in a static device array of SCORCH_STATIC_SCRATCH_BYTES that each GPU the library runs on holds until the
+ * process ends.  The call allocates nothing on the device (no hipMalloc, hipFree or allocating library routine).
+ *   - A problem whose plan needs more than SCORCH_STATIC_SCRATCH_BYTES (see scorch_spmm_plan_workspace_bytes) is
+ *     refused with SCORCH_ERR_UNSUPPORTED and a message naming both sizes; nothing is enqueued then.
+ *   - The pattern is analysed at every call (one wait on `stream` while the list sizes come back), then the
+ *     execution is enqueued and the call returns without waiting for it.
+ *   - All calls on one GPU share that GPU's array: calls that overlap in time on one GPU (two streams, two host
+ *     threads) race on it and give undefined results; calls on one stream are ordered and safe.  Nothing the previous
+ *     call left in the array is relied upon.
+ */
+#define SCORCH_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+scorch_status_t scorch_spmm_csr_static(int32_t m, int32_t k, int32_t n,
+                                       const int32_t *rowptr, const int32_t *colidx, const float *vals,
+                                       const float *B, int32_t ldb,
+                                       float *C, int32_t ldc,
+                                       void *stream);
+
 /* Frees the host handle only (the workspace belongs to the caller).  NULL is accepted. */
 scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan);
 

@@ -25,7 +25,7 @@ EXPORTS = (
     "scorch_spmm_csr", "scorch_spmm_plan_workspace_bytes", "scorch_spmm_plan", "scorch_spmm_csr_planned",
     "scorch_spmm_plan_destroy", "scorch_spmm_plan_info", "scorch_status_string", "scorch_last_error",
     "scorch_sddmm_csr", "scorch_sddmm_csr_planned", "scorch_spmm_csr_planned_epilogue", "scorch_coo_to_csr_rowptr",
-    "scorch_dcsr_to_csr_rowptr",
+    "scorch_dcsr_to_csr_rowptr", "scorch_spmm_csr_static",
 )
 
 
@@ -65,6 +65,8 @@ def load_library() -> ctypes.CDLL:
     i32, i64, vp = ctypes.c_int32, ctypes.c_int64, ctypes.c_void_p
     lib.scorch_spmm_csr.restype = i32
     lib.scorch_spmm_csr.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp]
+    lib.scorch_spmm_csr_static.restype = i32
+    lib.scorch_spmm_csr_static.argtypes = [i32, i32, i32, vp, vp, vp, vp, i32, vp, i32, vp]
     lib.scorch_spmm_plan_workspace_bytes.restype = i32
     lib.scorch_spmm_plan_workspace_bytes.argtypes = [i32, i32, i32, i64, ctypes.POINTER(ctypes.c_size_t)]
     lib.scorch_spmm_plan.restype = i32
@@ -127,6 +129,19 @@ def scorch_spmm_csr(m: int, k: int, n: int, rowptr: torch.Tensor, colidx: torch.
     _check(lib.scorch_spmm_csr(m, k, n, _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
                                _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(B, torch.float32, "B"), _ld(B, "B"),
                                _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))
+
+
+STATIC_SCRATCH_BYTES = 16 << 20
+
+
+def scorch_spmm_csr_static(m: int, k: int, n: int, rowptr: torch.Tensor, colidx: torch.Tensor, vals: torch.Tensor,
+                           B: torch.Tensor, C: torch.Tensor, stream: Optional[torch.cuda.Stream] = None) -> None:
+    """C[:m, :n] = A @ B[:k, :n] through the entry point that allocates nothing on the device (the plan lives in the
+    library's static scratch array; problems whose plan needs more than STATIC_SCRATCH_BYTES are refused)."""
+    lib = load_library()
+    _check(lib.scorch_spmm_csr_static(m, k, n, _dev_ptr(rowptr, torch.int32, "rowptr"), _dev_ptr(colidx, torch.int32, "colidx"),
+                                      _dev_ptr(vals, torch.float32, "vals"), _dev_ptr(B, torch.float32, "B"), _ld(B, "B"),
+                                      _dev_ptr(C, torch.float32, "C"), _ld(C, "C"), _stream_handle(stream)))
 
 
 def scorch_spmm_plan_workspace_bytes(m: int, k: int, n: int, nnz: int) -> int:

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG_DIR)
 CSRC = os.path.join(PKG_DIR, "csrc")
 OBJ_DIR = os.path.join(PKG_DIR, "_build")
 LIB_PATH = os.path.join(PKG_DIR, "libscorch_spmm.so")
-SOURCES = ["spmm_api.hip", "spmm_plan.hip", "spmm_exec.hip", "spmm_panel.hip", "sddmm_exec.hip"]
+SOURCES = ["spmm_api.hip", "spmm_plan.hip", "spmm_exec.hip", "spmm_panel.hip", "sddmm_exec.hip", "spmm_static.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # no packed-fp32 VALU forms: keep fp32 multiply-adds as plain v_fma_f32
