@@ -219,6 +219,78 @@ def time_graph_replay(res, torch, sp, steps_per_graph=20, replays=10):
     return (time.perf_counter() - t0) * 1e3 / (replays * steps_per_graph)
 
 
+def measure_practical_peak(torch, flush_buf):
+    """What this chip delivers, measured now, on the launch stream, to the access patterns an SpMM consists of:
+    a streaming read, a copy, and random gathers of whole 256/400/512-byte rows from tables that fit one die's L2 (2 MB),
+    that fit the 256 MB memory-side cache (96 MB) and that exceed both (2 GiB).  GB/s of useful bytes, best of 3 launches.
+    The probe kernels live in a library of their own (paper_2405_16883_amd/csrc/probes), not in the product."""
+    import ctypes
+
+    from paper_2405_16883_amd.build import PROBES_LIB_PATH
+    if not os.path.exists(PROBES_LIB_PATH):
+        raise FileNotFoundError(f"{PROBES_LIB_PATH} is missing: build it with __graft_entry__.build()")
+    lib = ctypes.CDLL(PROBES_LIB_PATH)
+    vp, i32, i64, u32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_size_t
+    lib.scorch_probe_stream_read.argtypes = [vp, sz, i32, vp, vp]
+    lib.scorch_probe_copy.argtypes = [vp, vp, sz, vp]
+    lib.scorch_probe_row_gather.argtypes = [vp, u32, u32, i32, i64, i32, vp, vp]
+    dev = "cuda:0"
+    stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+    sink = torch.zeros(64, dtype=torch.float32, device=dev)
+    big = torch.zeros(1 << 29, dtype=torch.float32, device=dev)  # 2 GiB table / copy destination
+
+    def best_ms(call, reps=3):
+        call()
+        torch.cuda.synchronize()
+        out = []
+        for _ in range(reps):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            rc = call()
+            b.record()
+            torch.cuda.synchronize()
+            assert rc == 0, "probe launch failed"
+            out.append(a.elapsed_time(b))
+        return min(out)
+
+    gib = 1 << 30
+    pk = {"unit": "GB/s of useful bytes", "hbm_spec_gbs": HBM_PEAK_GBS}
+    ms = best_ms(lambda: lib.scorch_probe_stream_read(big.data_ptr(), 2 * gib, 1, sink.data_ptr(), stream))
+    pk["stream_read_2GiB"] = 2 * gib / ms / 1e6
+    ms = best_ms(lambda: lib.scorch_probe_copy(flush_buf.data_ptr(), big.data_ptr(), gib, stream))
+    pk["copy_1GiB_read_plus_write"] = 2 * gib / ms / 1e6
+    groups, iters = 65536, 256
+    pk["row_gather"] = {}
+    for row_floats in (64, 100, 128):
+        row = {}
+        for label, table_bytes in (("table_2MB_fits_one_L2", 2 << 20), ("table_96MB_fits_memory_side_cache", 96 << 20),
+                                   ("table_2GiB_beyond_both", 2 * gib)):
+            rows = table_bytes // (row_floats * 4)
+            ms = best_ms(lambda: lib.scorch_probe_row_gather(big.data_ptr(), rows, row_floats, row_floats, groups, iters,
+                                                             sink.data_ptr(), stream))
+            row[label] = groups * iters * row_floats * 4 / ms / 1e6
+        pk["row_gather"][f"{row_floats * 4}B_rows"] = row
+    del big
+    torch.cuda.empty_cache()
+    return pk
+
+
+def practical_floor(p, bytes_min, uniq_cols, pk):
+    """Time a kernel would need that streams A and C at the measured streaming-read rate and fetches one whole row of B
+    per stored entry at the measured random-row-gather rate for rows of this width from a table of B's size (no reuse
+    of a row between entries: what a graph without locality offers beyond its hub rows).  Returned with its inputs."""
+    row_bytes = p.n * 4
+    width = "256B_rows" if row_bytes <= 256 else ("400B_rows" if row_bytes <= 400 else "512B_rows")
+    b_bytes = p.k * row_bytes
+    size = ("table_2MB_fits_one_L2" if b_bytes <= (3 << 20) else
+            "table_96MB_fits_memory_side_cache" if b_bytes <= (200 << 20) else "table_2GiB_beyond_both")
+    gather_gbs = pk["row_gather"][width][size]
+    stream_bytes = bytes_min - uniq_cols * row_bytes
+    t = stream_bytes / (pk["stream_read_2GiB"] * 1e9) + p.nnz * row_bytes / (gather_gbs * 1e9)
+    return {"seconds": t, "gather_rate_used": f"{width}/{size}", "gather_gbs": gather_gbs,
+            "gather_bytes": p.nnz * row_bytes, "streamed_bytes": stream_bytes}
+
+
 def cpu_baseline_and_check(res, torch, target_nnz=80_000_000):
     """Time the serial fp64 oracle on a contiguous block of rows (~target_nnz entries, 10-15 s) and compare GPU rows."""
     from oracle import spmm_csr_oracle  # the only place the benchmark touches the oracle
@@ -287,7 +359,9 @@ def main():
     ap.add_argument("--config", type=int, default=HEADLINE_CONFIG, help="workload 1..5 of the headline line")
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of the other four workloads")
+    ap.add_argument("--others", type=str, default="1,2,3,4,5", help="which of the other workloads get their short run (comma-separated)")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-practical", action="store_true", help="skip the bandwidth probes (practical_peak)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run one plain 1 GiB device copy (known traffic) so that a counter run can scale FETCH_SIZE/WRITE_SIZE")
     args = ap.parse_args()
@@ -299,7 +373,7 @@ def main():
     import torch
 
     import paper_2405_16883_amd as sp
-    from workloads import CONFIG_NAMES, make_config, min_traffic_bytes
+    from workloads import CONFIG_NAMES, count_unique_columns, make_config, min_traffic_bytes
 
     if not torch.cuda.is_available():
         print("bench.py: no GPU visible", file=sys.stderr)
@@ -312,6 +386,12 @@ def main():
 
     def flush():
         flush_buf.add_(1.0)
+
+    practical = None if args.no_practical else measure_practical_peak(torch, flush_buf)
+    if practical is not None:
+        g = practical["row_gather"]
+        log(f"[bench] practical peak: stream read {practical['stream_read_2GiB']:.0f} GB/s, copy {practical['copy_1GiB_read_plus_write']:.0f} GB/s; "
+            + "; ".join(f"{w} gathers " + "/".join(f"{v:.0f}" for v in g[w].values()) for w in g) + " GB/s (L2 / memory-side cache / beyond)")
 
     def run_config(cfg, steps, warmup, cold_steps):
         t0 = time.perf_counter()
@@ -351,6 +431,10 @@ def main():
                              "mode": {0: "gather", 1: "xcd_sliced_gather", 2: "lds_panel"}[info.mode],
                              "hot_columns": info.n_hot_columns, "hot_share": round(float(info.hot_share), 4)}})
         out["mode"] = out["plan"]["mode"]
+        if practical is not None:
+            fl = practical_floor(p, bytes_min, count_unique_columns(p), practical)
+            out["practical_floor"] = fl
+            out["frac_of_practical"] = fl["seconds"] / (out["event_ms_mean"] * 1e-3)
         tr_ = traffic.get(CONFIG_NAMES[cfg])
         if tr_:
             out["traffic"] = tr_["total_bytes"]
@@ -386,6 +470,10 @@ def main():
         "traffic_detail": tr,
         "frac_of_peak_on_measured_traffic": ((tr["total_bytes"] / (head["event_ms_mean"] * 1e-3) / 1e9 / HBM_PEAK_GBS)
                                              if tr else None),
+        # floor from the rates measured in this run (see practical_floor) over the measured time: above 1 means the
+        # kernel beats a reuse-free gather of one row of B per entry, i.e. it already gets reuse out of the caches
+        "frac_of_practical": head.get("frac_of_practical"),
+        "practical_floor": head.get("practical_floor"),
     }
     cpu = None if args.no_cpu else cpu_baseline_and_check(res, torch)
     if cpu is not None:
@@ -394,8 +482,9 @@ def main():
     del res
     others = {}
     if not args.no_others:
+        wanted = {int(x) for x in args.others.split(",") if x.strip()}
         for cfg in (1, 2, 3, 4, 5):
-            if cfg == args.config:
+            if cfg == args.config or cfg not in wanted:
                 continue
             torch.cuda.empty_cache()
             r, o = run_config(cfg, 50 if cfg != 4 else 20, 5, cold_steps=10 if cfg != 4 else 3)
@@ -422,7 +511,7 @@ def main():
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
                                                            "gbs_min_traffic", "frac_hbm", "cold_event_ms_mean",
                                                            "cold_frac_hbm", "plan_ms", "plan_free_event_ms_mean") + tuple(x for x in ("sddmm", "widenings") if x in o)
-                                        + tuple(x for x in ("mode", "traffic", "alu_roofline") if x in o)
+                                        + tuple(x for x in ("mode", "traffic", "alu_roofline", "frac_of_practical", "practical_floor") if x in o)
                                         + (("graph_replay_ms_per_step",) if "graph_replay_ms_per_step" in o else ())}
             del r
 
@@ -447,6 +536,7 @@ def main():
         "hbm_frac_of_peak": head["frac_hbm"],
         "cold_cache": {"event_ms_mean": head.get("cold_event_ms_mean"), "frac_hbm": head.get("cold_frac_hbm")},
         "roofline": roofline,
+        "practical_peak": practical,
         "cpu_baseline": cpu,
         "other_workloads": others,
     }

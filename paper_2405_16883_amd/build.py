@@ -50,5 +50,20 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+PROBES_LIB_PATH = os.path.join(PKG_DIR, "libscorch_probes.so")
+
+
+def build_probes(verbose: bool = False) -> str:
+    """Builds the benchmark's bandwidth probes into a library of their own (the product library never sees them)."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    if not os.path.exists(hipcc):
+        hipcc = "hipcc"
+    tmp = PROBES_LIB_PATH + f".tmp{os.getpid()}"
+    _run([hipcc, *HIPCC_FLAGS, "-shared", os.path.join(CSRC, "probes", "bandwidth_probes.hip"), "-o", tmp], verbose)
+    os.replace(tmp, PROBES_LIB_PATH)
+    return PROBES_LIB_PATH
+
+
 if __name__ == "__main__":
+    print(build_probes(verbose="-v" in sys.argv))
     print(build_library(verbose="-v" in sys.argv))
