@@ -68,6 +68,7 @@ scorch_status_t scorch_spmm_csr(int32_t m, int32_t k, int32_t n,
                                 void *stream);
 
 /*
+ * (Plumbing of this library; the paper has no counterpart: its kernels are generated per call on the CPU.)
  * Size, in bytes, of the device workspace a plan for an m x k matrix with nnz stored entries and
  * n dense columns needs (row lists, partial rows, and for some shapes a repacked copy of B).
  * It depends on the tuning read from the environment (see scorch_spmm_plan); call both with
@@ -97,10 +98,12 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * each column occurs and marks the most referenced columns (up to 64 MB of rows of B) as hot; execution then
  * reads only those rows of B with the default cache policy and the others with the streaming policy.
  * This changes no result bit.
- * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>,sdblk=.."
+ * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>,sdblk=..,fix=.."
  * overrides the built-in parameter choice (for experiments; sliced = 0, 1 (= 32), 32, 64 or 128 columns of B per
  * accelerator-die slice, panel = 0, 1 or 2; sdblk = blocks of columns of A per accelerator die in the planned
- * SDDMM, 0 = row-wise kernel, read at every SDDMM call).
+ * SDDMM, 0 = row-wise kernel; fix = 1 or 2: partial rows are added inside the fused launch, by the piece that finishes last, instead
+ * of by a second launch).
+ * The variable is read when a plan is made (and by scorch_spmm_plan_workspace_bytes), never by an execution call.
  */
 scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
                                  const int32_t *rowptr, const int32_t *colidx,
@@ -109,8 +112,10 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
                                  scorch_spmm_plan_t **plan_out);
 
 /*
- * Planned SpMM: same result contract as scorch_spmm_csr, executed through the plan's row lists:
- * one fused launch, plus one small fix-up launch when rows were split across workgroups; for wide
+ * Planned SpMM: the operation at the top of this file (paper, Section 4.2), i.e. the same result contract as
+ * scorch_spmm_csr, executed through the plan's row lists (the plan itself has no counterpart in the paper):
+ * one fused launch, plus one small fix-up launch when rows were split across workgroups (the pieces
+ * leave partial rows in the workspace, which are added in piece order); for wide
  * B with few rows a pre-pass first copies B into column-slice-major order so that each accelerator
  * die keeps its slice of B in its own L2; matrices with a few percent of their entries stored and
  * strictly increasing columns in every row go to a kernel that streams that copy of B through LDS
@@ -166,12 +171,15 @@ scorch_status_t scorch_spmm_csr_static(int32_t m, int32_t k, int32_t n,
                                        float *C, int32_t ldc,
                                        void *stream);
 
-/* Frees the host handle only (the workspace belongs to the caller).  NULL is accepted. */
+/* (Plumbing; no counterpart in the paper.)  Frees the host handle only (the workspace belongs to the caller).  NULL is
+ * accepted. */
 scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan);
 
 /*
- * What a plan contains.  Offsets are byte offsets into the caller's workspace:
+ * (Plumbing; no counterpart in the paper.)  What a plan contains, for tests and tools.  Offsets are byte offsets into the
+ * caller's workspace:
  *   win_row_start  int32[n_windows + 1]
+ *   win_stage      int32[n_windows][2]         entries a window stages (see off_win_stage)
  *   wave_rows      int32[n_wave_rows]          ascending row ids
  *   items          int32[n_items][4]           (row, p_begin, p_end, partial slot or -1)
  *   split          int32[n_split_rows][4]      (row, first slot, pieces, 0)
@@ -189,6 +197,8 @@ typedef struct scorch_spmm_plan_info {
     int32_t n_hot_columns; /* columns whose rows of B keep the default cache policy (0: no hot/cold split) */
     float hot_share;       /* share of the stored entries that point at those columns (beyond 2^24 entries:
                               of an evenly spread sample of 2^23..2^24 of them, which is what ranks the columns) */
+    uint64_t off_win_stage; /* int32[n_windows][2]: (first entry, number of entries) between the first and the last
+                               short row of the window, capped at 320 entries; (0, -1) for a window without short rows */
 } scorch_spmm_plan_info_t;
 
 scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spmm_plan_info_t *out);
@@ -241,10 +251,11 @@ scorch_status_t scorch_dcsr_to_csr_rowptr(int32_t m, int32_t n_stored_rows, cons
                                           const int32_t *row_pos, int32_t *rowptr_out, int32_t *bad_flag,
                                           void *stream);
 
-/* Static text for a status code. */
+/* (Plumbing; no counterpart in the paper.)  Static text for a status code. */
 const char *scorch_status_string(scorch_status_t status);
 
-/* Thread-local description of the most recent failure in this thread ("" if none). */
+/* (Plumbing; no counterpart in the paper.)  Thread-local description of the most recent failure in this thread ("" if
+ * none). */
 const char *scorch_last_error(void);
 
 #ifdef __cplusplus

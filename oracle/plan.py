@@ -10,6 +10,8 @@ with sorts, searches and Python loops, no parallel tricks:
   * windows     row i has merge-path key  key_i = rowptr[i] + ALPHA*i  (strictly increasing);
                 window w owns the rows with key in [w*BN, (w+1)*BN); win_row_start[w] is the
                 first such row; there are NW = (nnz + ALPHA*m)//BN + 1 windows
+  * win_stage   per window (first entry, number of entries) from the first to the last short row among its first
+                64 rows, the number capped at STAGE_MAX = 320; (0, -1) when it has no short row
   * wave_rows   the class-1 row ids, ascending
   * items       for every class-2 row, ascending: its nnz range cut into pieces of at most BCH;
                 a row cut into more than one piece gets consecutive partial-sum slots
@@ -38,6 +40,17 @@ def plan_oracle(rowptr: np.ndarray, BN: int, ALPHA: int, LW: int, CH: int, BCH: 
     win_row_start = np.searchsorted(key, np.arange(NW + 1, dtype=np.int64) * BN, side="left").astype(np.int32)
     win_row_start[NW] = m
 
+    STAGE_MAX, WINDOW_ROWS_MAX = 320, 64
+    win_stage = np.zeros((NW, 2), dtype=np.int32)
+    for w in range(NW):
+        r0, r1 = int(win_row_start[w]), min(int(win_row_start[w + 1]), int(win_row_start[w]) + WINDOW_ROWS_MAX)
+        short = [r for r in range(r0, r1) if cls[r] == 0]
+        if short:
+            beg, end = int(rp[short[0]]), int(rp[short[-1] + 1])
+            win_stage[w] = (beg, min(end - beg, STAGE_MAX))
+        else:
+            win_stage[w] = (0, -1)
+
     wave_rows = np.nonzero(cls == 1)[0].astype(np.int32)
 
     items, split = [], []
@@ -56,6 +69,7 @@ def plan_oracle(rowptr: np.ndarray, BN: int, ALPHA: int, LW: int, CH: int, BCH: 
     return {
         "row_class": cls,
         "win_row_start": win_row_start,
+        "win_stage": win_stage,
         "wave_rows": wave_rows,
         "items": np.array(items, dtype=np.int32).reshape(-1, 4),
         "split": np.array(split, dtype=np.int32).reshape(-1, 4),

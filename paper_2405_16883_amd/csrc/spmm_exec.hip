@@ -191,6 +191,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     __shared__ float s_red[kWavesPerBlock * TW];
     // one-lane groups (n <= 4) only: the products of a window's entries, summed per row afterwards
     __shared__ __attribute__((aligned(16))) float s_prod[G == 1 ? kWavesPerBlock * kStageMax * V : 1];
+    __shared__ int s_flag;  // piece of a split row: this workgroup drew the row's last ticket
 
     const int tid = threadIdx.x;
     const int wv = tid >> 6;
@@ -258,9 +259,58 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
                     if constexpr (V == 1) r = s;
                     else r[i] = s;
                 }
-                // a partial row gets its epilogue in the fix-up, after the pieces are added
+                // a partial row gets its epilogue after the pieces are added
                 if (it.w < 0) r = apply_epilogue<V>(r, a.bias ? a.bias + coff[t] : nullptr, a.act);
-                vstore<V, NTC, UA>(dst + coff[t], r);
+                if (it.w < 0) vstore<V, NTC, UA>(dst + coff[t], r);
+                else if (a.fold == 2) {
+                    // experiment: every float of the partial row as a device-scope atomic store (written through this
+                    // die's L2), so that no L2 write-back is needed before the ticket
+#pragma unroll
+                    for (int i = 0; i < V; ++i) {
+                        float x;
+                        if constexpr (V == 1) x = r;
+                        else x = r[i];
+                        __hip_atomic_store(dst + coff[t] + i, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
+                } else vstore<V, false, UA>(dst + coff[t], r);
+            }
+        }
+        if (it.w < 0 || a.tickets == nullptr) return;  // whole row done, or the fix-up launch adds the partial rows
+        // ---- piece of a split row: the workgroup that arrives last adds up the row's partial rows ----
+        // Every piece publishes its partial row (device-scope release), then takes a ticket of the row (integer
+        // atomic); the piece that draws the last ticket knows that all partial rows are visible (device-scope
+        // acquire) and adds them in piece order, whichever piece it is: the sum does not depend on the arrival order,
+        // and no floating-point atomics are involved.  The counter is left at zero for the next launch.
+        const int row_p0 = a.rowptr[it.x], row_p1 = a.rowptr[it.x + 1];
+        const int piece = (it.y - row_p0) / a.BCH;
+        const int pieces = (row_p1 - row_p0 + a.BCH - 1) / a.BCH;
+        const int first = it.w - piece;
+        if (wv == 0) {
+            if (a.fold == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // experiment: the written-through stores have completed
+            else __threadfence();  // release: this wavefront's stores of the partial row, device-wide
+            if (lane == 0) {
+                int32_t *tk = a.tickets + ((int64_t)first * a.ncoltiles + ct);
+                const int old = atomicAdd(tk, 1);
+                const int is_last = old == pieces - 1;
+                if (is_last) atomicExch(tk, 0);
+                s_flag = is_last;
+            }
+        }
+        __syncthreads();
+        if (!s_flag) return;
+        if (a.fold != 2) __threadfence();  // acquire: the other pieces' partial rows
+        {
+            const float *src = a.partials + (int64_t)first * a.partial_stride;
+            float *dst = a.C + (int64_t)it.x * a.ldc;
+            const int cbeg = (int)ct * TW, cend = min(a.n, cbeg + TW);
+            for (int c = cbeg + tid; c < cend; c += kBlock) {
+                // read past this die's L2: the other pieces may have run on other dies
+                float sum = __hip_atomic_load(src + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int i = 1; i < pieces; ++i)
+                    sum += __hip_atomic_load(src + (int64_t)i * a.partial_stride + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if (a.bias) sum += a.bias[c];
+                if (a.act == 1) sum = fmaxf(sum, 0.f);
+                dst[c] = sum;
             }
         }
         return;
@@ -289,20 +339,17 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     if (w >= a.n_windows) return;
     const int r0 = a.win_row_start[w];
     const int r1 = a.win_row_start[w + 1];
+    // which entries the window stages is known from the plan, so colidx/vals are requested together with the row
+    // pointers instead of after them
+    const int2 stg = a.win_stage[w];
+    if (stg.y < 0) return;  // no short row in this window
     const int nr = min(r1 - r0, kWindowRowsMax);
-    if (nr <= 0) return;
+    const int sbeg = stg.x, cnt = stg.y;
     const int rpv = a.rowptr[r0 + min(lane, nr)];
     const int rlast = a.rowptr[r0 + nr];
     int rnext = __shfl_down(rpv, 1, kWave);
     if (lane == kWave - 1) rnext = rlast;
     const bool is_short = lane < nr && (rnext - rpv) <= a.LW;
-    const unsigned long long bal = __ballot(is_short);
-    if (bal == 0ull) return;
-    const int first = __builtin_ctzll(bal);
-    const int last = 63 - __builtin_clzll(bal);
-    const int sbeg = __shfl(rpv, first, kWave);
-    const int send = __shfl(rnext, last, kWave);
-    const int cnt = min(send - sbeg, kStageMax);
     if constexpr (G == 1) {
         // SpMV and its neighbours (n <= 4, one lane per entry): a window has far fewer rows than the wavefront has
         // lanes, so the lanes split the window's *entries* instead of its rows: every lane reads its entries
@@ -705,9 +752,20 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     a.n = plan->n;
     char *ws = plan->workspace;
     a.win_row_start = reinterpret_cast<const int32_t *>(ws + plan->layout.off_win);
+    a.win_stage = reinterpret_cast<const int2 *>(ws + plan->layout.off_stage);
     a.wave_rows = reinterpret_cast<const int32_t *>(ws + plan->layout.off_wave);
     a.items = reinterpret_cast<const int4 *>(ws + plan->layout.off_items);
     a.partials = reinterpret_cast<float *>(ws + plan->layout.off_partials);
+    // Partial rows of split rows are added by a second, small launch.  Adding them inside the fused launch, by the piece
+    // that arrives last, is built and tested but off by default (fix=1 or fix=2 in the tuning text turns it on): with
+    // proper device-scope release/acquire fences every piece makes its die write back and invalidate its L2, which
+    // cost 90 us on the mid-size graph workload (213 against 123 us); with written-through atomic stores instead of
+    // fences (fix=2) it saves 3.5 us, but then the order between the partial row and the ticket rests on the completion
+    // of written-through stores, which the language-level memory model does not promise.
+    const bool fold = plan->n_split > 0 && plan->tuning.fix > 0;
+    a.tickets = fold ? reinterpret_cast<int32_t *>(ws + plan->layout.off_tickets) : nullptr;
+    a.fold = fold ? (plan->tuning.fix == 2 ? 2 : 1) : 0;
+    a.BCH = plan->params.BCH;
     a.n_windows = (int32_t)plan->layout.n_windows;
     a.n_wave_rows = plan->n_wave;
     a.n_items = plan->n_items;
@@ -746,7 +804,7 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "launch spmm_fused_kernel");
     }
-    if (plan->n_split > 0) {
+    if (plan->n_split > 0 && !fold) {
         FixupArgs f{};
         f.split = reinterpret_cast<const int4 *>(ws + plan->layout.off_split);
         f.partials = a.partials;

@@ -46,8 +46,9 @@ Tuning read_tuning_from_env();
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t);
 
 struct WorkspaceLayout {
-    uint64_t off_counts, off_totals, off_win, off_wave, off_items, off_split, off_partials, off_bpack, off_coldeg,
-        off_hotmask, off_degbins, total;
+    uint64_t off_counts, off_totals, off_win, off_stage, off_wave, off_items, off_split, off_partials, off_tickets, off_bpack,
+        off_coldeg, off_hotmask, off_degbins, total;
+    int64_t ticket_tiles;  // arrival counters per split row: one for every column tile a launch may use
     int64_t n_windows, nblk;
     int64_t cap_wave, cap_items, cap_split, cap_slots;
     int32_t partial_stride;
@@ -64,9 +65,13 @@ struct ExecArgs {
     int64_t ldb, ldc;
     int32_t m, n;
     const int32_t *win_row_start;
+    const int2 *win_stage;  // per window: (first staged entry, number of staged entries) of its short rows; y < 0: no short row
     const int32_t *wave_rows;
     const int4 *items;
     float *partials;
+    int32_t *tickets;  // arrival counters of the split rows (nullptr: partial rows are added by the fix-up launch)
+    int32_t BCH;       // entries per piece of a long row
+    int32_t fold;      // 0: fix-up launch; 1: last piece adds the partial rows (fences); 2: the same with written-through atomic stores
     int32_t n_windows, n_wave_rows, n_items;
     int32_t nb_items, nb_wave, nb_win;  // workgroups per path, per column tile
     int32_t partial_stride;

@@ -175,6 +175,36 @@ __global__ __launch_bounds__(kBlock) void plan_window_kernel(const int32_t *rowp
     win_row_start[w] = (int32_t)lo;
 }
 
+// What a window's wavefront stages in LDS: the entries from the first to the last short row of the window (rows of
+// up to LW entries; the window holds at most 64 rows), at most stage_max of them.  Stored in the plan so that the
+// execution kernel can fetch colidx/vals at once instead of waiting for the row pointers first.
+// stage[w] = (first entry, number of entries), or (0, -1) for a window without short rows.
+__global__ __launch_bounds__(kBlock) void plan_stage_kernel(const int32_t *rowptr, const int32_t *win_row_start,
+                                                            int64_t n_windows, int32_t LW, int32_t stage_max,
+                                                            int2 *stage) {
+    const int64_t w = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (w >= n_windows) return;
+    const int r0 = win_row_start[w];
+    const int r1 = min(win_row_start[w + 1], r0 + kWindowRowsMax);
+    int first = -1, last = -1;
+    int prev = r0 < r1 ? rowptr[r0] : 0;
+    int sbeg = 0, send = 0;
+    for (int r = r0; r < r1; ++r) {
+        const int next = rowptr[r + 1];
+        if (next - prev <= LW) {
+            if (first < 0) {
+                first = r;
+                sbeg = prev;
+            }
+            last = r;
+            send = next;
+        }
+        prev = next;
+    }
+    stage[w] = first < 0 ? make_int2(0, -1) : make_int2(sbeg, min(send - sbeg, stage_max));
+    (void)last;
+}
+
 // Sets *flag when some row's column indices are not strictly increasing (one wavefront per row).
 __global__ __launch_bounds__(kBlock) void plan_sorted_kernel(const int32_t *rowptr, const int32_t *colidx, int32_t m,
                                                              int32_t *flag) {
@@ -468,6 +498,8 @@ WorkspaceLayout layout_workspace(int32_t m, int32_t k, int64_t nnz, int32_t n, c
     off = align_up(off + kQ * 4, 256);
     L.off_win = off;
     off = align_up(off + (uint64_t)(L.n_windows + 1) * 4, 256);
+    L.off_stage = off;
+    off = align_up(off + (uint64_t)L.n_windows * 8, 256);
     L.off_wave = off;
     off = align_up(off + (uint64_t)L.cap_wave * 4, 256);
     L.off_items = off;
@@ -476,6 +508,10 @@ WorkspaceLayout layout_workspace(int32_t m, int32_t k, int64_t nnz, int32_t n, c
     off = align_up(off + (uint64_t)L.cap_split * 16, 256);
     L.off_partials = off;
     off = align_up(off + (uint64_t)L.cap_slots * L.partial_stride * 4, 256);
+    // arrival counters: a split row has one per column tile of the launch; the narrowest tile any mapping uses is 16 columns
+    L.ticket_tiles = std::max<int64_t>(1, ((int64_t)n + 15) / 16);
+    L.off_tickets = off;
+    off = align_up(off + (uint64_t)L.cap_slots * L.ticket_tiles * 4, 256);  // indexed by a split row's first slot
     L.off_bpack = off;
     if (p.PACK || p.PANEL) off = align_up(off + (uint64_t)k * ((n + 2 * kPanelCols - 1) / (2 * kPanelCols)) * (2 * kPanelCols) * 4, 256);
     L.off_coldeg = off;
@@ -544,6 +580,16 @@ scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, cons
                            reinterpret_cast<int32_t *>(ws + L.off_win));
         hipError_t e = hipGetLastError();
         if (e != hipSuccess) return hip_fail(e, "launch plan_window_kernel");
+        hipLaunchKernelGGL(plan_stage_kernel, dim3((uint32_t)wblocks), dim3(kBlock), 0, stream, rowptr,
+                           reinterpret_cast<const int32_t *>(ws + L.off_win), L.n_windows, plan->params.LW, kStageMax,
+                           reinterpret_cast<int2 *>(ws + L.off_stage));
+        e = hipGetLastError();
+        if (e != hipSuccess) return hip_fail(e, "launch plan_stage_kernel");
+        // the arrival counters of split rows start at zero; every launch leaves them at zero again
+        if (L.cap_slots > 0) {
+            e = hipMemsetAsync(ws + L.off_tickets, 0, (size_t)L.cap_slots * L.ticket_tiles * 4, stream);
+            if (e != hipSuccess) return hip_fail(e, "clear arrival counters");
+        }
         e = hipStreamSynchronize(stream);
         if (e != hipSuccess) return hip_fail(e, "wait for plan kernels");
     }

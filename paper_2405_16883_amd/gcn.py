@@ -50,6 +50,9 @@ class GcnLayer:
             return out
         Y = torch.empty((self.m, n_in), dtype=torch.float32, device=H.device)
         _b.scorch_spmm_csr_planned(self._plan(n_in), self.rowptr, self.colidx, self.vals, H, Y, stream=stream)
+        # Here the dense product comes last, so bias and activation are the epilogue of a DENSE operation: they stay
+        # with the dense library (addmm adds the bias inside the product, relu_ runs on its result), exactly as the
+        # paper hands dense work to PyTorch.  Nothing sparse is computed in Python.
         out = torch.mm(Y, W) if bias is None else torch.addmm(bias, Y, W)
         return torch.relu_(out) if relu else out
 

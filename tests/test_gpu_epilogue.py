@@ -36,7 +36,8 @@ def run_epilogue(p, bias, relu, exact=False, label="", tune=None):
         assert np.array_equal(C, plain), f"{label}: identity epilogue differs from the plain call"
 
 
-TUNES = [None, "bn=64,alpha=2,lw=8,ch=32,bch=64", "sliced=1,pack=1", "panel=1", "panel=2", "panel=0"]
+TUNES = [None, "bn=64,alpha=2,lw=8,ch=32,bch=64", "sliced=1,pack=1", "panel=1", "panel=2", "panel=0",
+         "bn=64,alpha=2,lw=8,ch=32,bch=64,fix=1"]
 
 
 @pytest.mark.parametrize("tune", TUNES)

@@ -18,7 +18,8 @@ pytestmark = pytest.mark.gpu
 SMALL = [(1, 1.0), (2, 0.12), (3, 0.08), (4, 0.006), (5, 0.06)]
 # parameter sets that force every execution path (windows, wave rows, single- and multi-piece block rows)
 TUNES = [None, "bn=64,alpha=2,lw=8,ch=32,bch=64,u=4,nt=0", "bn=256,lw=64,ch=256,bch=256,u=8,nt=3",
-         "bn=128,lw=0,ch=64,bch=128", "bn=32,alpha=1,lw=64,ch=64,bch=1000000", "hot=16,ch=64,bch=128", "hot=1"]
+         "bn=128,lw=0,ch=64,bch=128", "bn=32,alpha=1,lw=64,ch=64,bch=1000000", "hot=16,ch=64,bch=128", "hot=1",
+         "bn=64,alpha=2,lw=8,ch=32,bch=64,fix=1"]  # fix=1: partial rows of split rows added inside the fused launch
 
 
 def run_both(p, ldc=None, exact=False, label=""):
@@ -263,7 +264,7 @@ def test_plan_lists_match_the_plan_oracle_bit_for_bit(cfg, scale, tune):
         want = plan_oracle(p.rowptr, info.BN, info.ALPHA, info.LW, info.CH, info.BCH)
         assert info.nnz == p.nnz and info.n_short_rows == int(want["n_short"])
         assert info.n_partial_slots == int(want["n_slots"])
-        for key in ("win_row_start", "wave_rows", "items", "split"):
+        for key in ("win_row_start", "win_stage", "wave_rows", "items", "split"):
             assert got[key].shape == want[key].shape, key
             assert np.array_equal(got[key], want[key]), key
         plan.destroy()
@@ -277,7 +278,7 @@ def test_plan_edge_patterns_match_oracle():
             plan = d.make_plan()
             info, got = read_plan_arrays(plan)
             want = plan_oracle(p.rowptr, info.BN, info.ALPHA, info.LW, info.CH, info.BCH)
-            for key in ("win_row_start", "wave_rows", "items", "split"):
+            for key in ("win_row_start", "win_stage", "wave_rows", "items", "split"):
                 assert np.array_equal(got[key], want[key]), (key, lens[:4])
             plan.destroy()
 
@@ -353,3 +354,31 @@ def test_sparse_activation_times_dense_weight_shape(k, density):
     p = csr_from_row_lengths(lens, k, 256, seed=k)
     run_both(p, label=f"batch 64 x {k} @ {k} x 256, density {density}")
     run_both(integer_valued(p, seed=1), exact=True, label=f"batch 64 x {k} int")
+
+
+@pytest.mark.parametrize("n,tune", [(128, "ch=64,bch=64"), (100, "ch=64,bch=128"), (1040, "ch=64,bch=64"), (256, "sliced=1,pack=1,ch=64,bch=64"),
+                                    (256, "sliced=64,ch=64,bch=96"), (3, "ch=64,bch=64"), (64, "hot=4,ch=64,bch=64")])
+def test_split_rows_added_inside_the_launch_match_the_second_launch_bit_for_bit(n, tune):
+    """Rows cut into many pieces (up to 150 per row, several column tiles or XCD slices).  Default: a second launch
+    adds the partial rows.  fix=1 / fix=2: the piece that arrives last adds them, in piece order, so the result equals
+    that of the second launch bit for bit at every repetition (the arrival order changes from run to run, the sum
+    must not), and the arrival counters are back at zero after every launch (else the next one would go wrong)."""
+    rng = np.random.default_rng(n)
+    lens = np.concatenate([rng.integers(0, 60, size=300), [9600, 5000, 0, 1300, 700, 130, 129, 128, 65, 64]])
+    rng.shuffle(lens)
+    p = csr_from_row_lengths(lens, 900, n, seed=n + 7, duplicates=True)
+    d = DeviceProblem(p)
+    with tuning(tune):
+        plan = d.make_plan()
+        assert plan.info().n_split_rows >= 5
+        want = d.run_planned(plan).copy()
+        plan.destroy()
+    check_against_oracle(p, want, d.ldc, label=f"two launches n={n} [{tune}]")
+    for fix in (1, 2):
+        with tuning(tune + f",fix={fix}"):
+            plan = d.make_plan()
+            for rep in range(12):
+                got = d.run_planned(plan)
+                assert np.array_equal(got, want), f"fix={fix} differs from the fix-up launch at repetition {rep} (n={n}, {tune})"
+            plan.destroy()
+            run_both(integer_valued(p, seed=n), exact=True, label=f"fix={fix} int n={n} [{tune}]")

@@ -18,6 +18,20 @@ def check_plan(rowptr, P, BN, ALPHA, LW, CH, BCH):
         if w[i + 1] > w[i]:
             span = rp[w[i + 1] - 1] - rp[w[i]]  # distance between first and last row start
             assert span < BN
+    # what a window stages: exactly the span from its first to its last short row, which holds every entry of every
+    # short row of the window (BN + LW <= 320 entries, so the cap never cuts a short row)
+    st = P["win_stage"].astype(np.int64)
+    assert st.shape == (len(w) - 1, 2) and BN + LW <= 320
+    for i in range(len(w) - 1):
+        rows = np.arange(w[i], w[i + 1])
+        sh = rows[lens[rows] <= LW]
+        if len(sh) == 0:
+            assert st[i].tolist() == [0, -1]
+        else:
+            beg, cnt = st[i]
+            assert beg == rp[sh[0]] and 0 <= cnt <= 320
+            assert np.all(rp[sh] >= beg) and np.all(rp[sh + 1] <= beg + cnt)
+            assert cnt == min(rp[sh[-1] + 1] - beg, 320)
     covered = np.zeros(m, dtype=np.int64)
     short = lens <= LW
     covered[short] += 1  # every short row is inside exactly one window (partition above)
@@ -62,6 +76,11 @@ def test_plan_edge_cases():
     assert P["row_class"].tolist() == [1, 2, 2, 2, 0, 1, 0]
     assert P["items"][:, 3].tolist() == [-1, -1, 0, 1]
     assert P["split"].tolist() == [[3, 0, 2, 0]]
+    # row pointers 0 64 129 257 386 402 419 419, keys rowptr[i] + 2 i = 0 66 133 263 394 412 431, windows of 64 key units:
+    # rows 0..3 sit alone in windows 0, 1, 2, 4; rows 4, 5, 6 share window 6, whose short rows are 4 (16 entries) and 6
+    # (empty), so it stages entries 386 .. 419 (the medium row 5 lies in between and is staged along)
+    assert P["win_row_start"].tolist() == [0, 1, 2, 3, 3, 4, 4, 7]
+    assert P["win_stage"].tolist() == [[0, -1], [0, -1], [0, -1], [0, -1], [0, -1], [0, -1], [386, 33]]
 
 
 def test_coo_rowptr_oracle_against_the_generators_own_row_pointers():
