@@ -78,6 +78,34 @@ def plan_oracle(rowptr: np.ndarray, BN: int, ALPHA: int, LW: int, CH: int, BCH: 
     }
 
 
+def hot_columns_oracle(colidx: np.ndarray, k: int, n: int, budget_kb: int):
+    """Which columns of A the planner marks as hot (their rows of B keep the default cache policy), stated plainly:
+    count how often every column occurs; put the counts into bins, 16 per power of two (bin 0: never occurs; a count x
+    with highest set bit e falls into bin 16 e + (the four bits below the highest) + 1); take whole bins from the
+    largest counts downwards while their columns, at one row of B rounded up to 128-byte lines each, fit budget_kb KB.
+    Returns (number of hot columns, share of the stored entries that point at them).  No counterpart in the paper:
+    parity unpinned against it, like the rest of the plan; results never depend on the marking."""
+    deg = np.bincount(np.asarray(colidx, dtype=np.int64), minlength=k)
+
+    def degree_bin(x: int) -> int:
+        if x <= 0:
+            return 0
+        e = int(x).bit_length() - 1
+        frac = (x >> (e - 4)) & 15 if e >= 4 else (x << (4 - e)) & 15
+        return e * 16 + frac + 1
+
+    bins = np.array([degree_bin(int(x)) for x in deg])
+    max_rows = max(1, budget_kb * 1024 // (((n * 4 + 127) // 128) * 128))
+    rows, entries = 0, 0
+    for b in range(int(bins.max()) if len(bins) else 0, 0, -1):
+        cnt = int((bins == b).sum())
+        if rows + cnt > max_rows:
+            break
+        rows += cnt
+        entries += int(deg[bins == b].sum())
+    return rows, (entries / len(colidx) if len(colidx) else 0.0)
+
+
 def coo_rowptr_oracle(m: int, row_idx: np.ndarray) -> np.ndarray:
     """Row pointers of a coordinate list (paper, Appendix C, coordinate format) whose entries are sorted by row:
     rowptr[i] = number of entries with row < i, i.e. the running sum of the per-row counts."""

@@ -32,10 +32,27 @@ __device__ __forceinline__ const float *b_row(const float *base, int c, uint32_t
 // One batch of U staged entries e, e+es, ... of a row:  acc[t] += val * B[col, boff[t] .. +V).  The U gathers
 // are issued before the first multiply so that U reads of B rows are in flight per group.  PRED: entries at or
 // past e_end are skipped (last batch of a row); otherwise the batch is whole and nothing is tested per entry.
-template <int V, int T, int U, bool UA, bool HOT, bool PRED>
+// How the rows of B outside the hot set are read (hot/cold variants only).  0: streaming (non-temporal) loads, the
+// default.  1..3: experiments with the other cache-policy bits of gfx950 loads, issued as buffer loads so that the
+// bits can be chosen: 1 = device scope (sc1: not kept in the vector L1), 2 = system scope (sc0 sc1), 3 = sc1 + nt.
+struct ColdPath {
+    __amdgpu_buffer_rsrc_t rsrc;  // covers B (only used when B is smaller than 4 GB)
+    uint32_t ldb_bytes;
+};
+template <int COLD> __device__ __forceinline__ Vec<4>::type cold_load(const ColdPath &cp, uint32_t byte_off) {
+    typedef int i4 __attribute__((ext_vector_type(4)));
+    constexpr int aux = COLD == 1 ? 16 : (COLD == 2 ? 17 : 18);
+    const i4 raw = __builtin_amdgcn_raw_buffer_load_b128(cp.rsrc, (int)byte_off, 0, aux);
+    Vec<4>::type x;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = __int_as_float(raw[i]);
+    return x;
+}
+
+template <int V, int T, int U, bool UA, bool HOT, bool PRED, int COLD = 0>
 __device__ __forceinline__ void gather_batch(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
                                              int e, int e_end, int es, const float *const (&bbase)[T],
-                                             uint32_t ldb) {
+                                             uint32_t ldb, const ColdPath *cp = nullptr, const int *boffb = nullptr) {
     using vec = typename Vec<V>::type;
     vec x[U][T];
     float v[U];
@@ -62,7 +79,8 @@ __device__ __forceinline__ void gather_batch(typename Vec<V>::type (&acc)[T], co
                     // the empty statements keep this load from being merged with the one of the other branch
                     // (hoisted above or sunk below the branch, the merged load loses the streaming policy)
                     asm volatile("");
-                    x[u][t] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(bp));
+                    if constexpr (COLD == 0 || V != 4) x[u][t] = __builtin_nontemporal_load(reinterpret_cast<const vec *>(bp));
+                    else x[u][t] = cold_load<COLD>(*cp, (uint32_t)cu * cp->ldb_bytes + (uint32_t)boffb[t]);
                     asm volatile("");
                 }
             } else {
@@ -80,18 +98,22 @@ __device__ __forceinline__ void gather_batch(typename Vec<V>::type (&acc)[T], co
 // one partial batch.  boff[t] is a readable offset in every lane (lanes past column n point at the last
 // vector of the row), so the loads carry no column test; `active` is false in the lanes whose first vector lies
 // past column n: they skip the row altogether.
-template <int V, int T, int U, bool UA, bool HOT = false>
+template <int V, int T, int U, bool UA, bool HOT = false, int COLD = 0>
 __device__ __forceinline__ void gather_fma(typename Vec<V>::type (&acc)[T], const int *lcol, const float *lval,
                                            int e0, int e_end, int es, const float *Bc, uint32_t ldb, bool active,
-                                           const int (&boff)[T]) {
+                                           const int (&boff)[T], const ColdPath *cp = nullptr) {
     if (!active) return;
     const float *bbase[T];
+    int boffb[T];
 #pragma unroll
-    for (int t = 0; t < T; ++t) bbase[t] = Bc + boff[t];
+    for (int t = 0; t < T; ++t) {
+        bbase[t] = Bc + boff[t];
+        boffb[t] = boff[t] * 4;
+    }
     int e = e0;
     for (; e + (U - 1) * es < e_end; e += U * es)
-        gather_batch<V, T, U, UA, HOT, false>(acc, lcol, lval, e, e_end, es, bbase, ldb);
-    if (e < e_end) gather_batch<V, T, U, UA, HOT, true>(acc, lcol, lval, e, e_end, es, bbase, ldb);
+        gather_batch<V, T, U, UA, HOT, false, COLD>(acc, lcol, lval, e, e_end, es, bbase, ldb, cp, boffb);
+    if (e < e_end) gather_batch<V, T, U, UA, HOT, true, COLD>(acc, lcol, lval, e, e_end, es, bbase, ldb, cp, boffb);
 }
 
 // Adds up the S = 64/G lane groups of a wavefront (xor butterfly over the lane distances G..32; DPP,
@@ -116,12 +138,12 @@ __device__ __forceinline__ int mark_hot(int c, const uint32_t *mask) {
     return c | (int)(((mask[c >> 5] >> (c & 31)) & 1u) << 31);
 }
 
-template <int V, int G, int T, int U, bool NTA, bool UA, bool HOT = false>
+template <int V, int G, int T, int U, bool NTA, bool UA, bool HOT = false, int COLD = 0>
 __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], int *lcol, float *lval, int lane,
                                                int grp, int pfirst, int p1, int stride, const int32_t *colidx,
                                                const float *vals, const float *Bc, uint32_t ldb,
                                                bool active, const int (&boff)[T],
-                                               const uint32_t *hotmask = nullptr) {
+                                               const uint32_t *hotmask = nullptr, const ColdPath *cp = nullptr) {
     constexpr int S = kWave / G;
     if constexpr (G == 1 && T == 1 && !HOT) {
         // One-lane groups (n <= 4): every lane owns the entries pfirst + lane + i * stride and needs no broadcast, so
@@ -168,14 +190,14 @@ __device__ __forceinline__ void row_accumulate(typename Vec<V>::type (&acc)[T], 
         }
         wave_lds_sync();
         const int cnt = min(kWave, p1 - base);
-        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, grp, cnt, S, Bc, ldb, active, boff);
+        gather_fma<V, T, U, UA, HOT, COLD>(acc, lcol, lval, grp, cnt, S, Bc, ldb, active, boff, cp);
         wave_lds_sync();
     }
 }
 
 constexpr int smem_ints_per_wave() { return 2 * kStageMax + kWindowRowsMax + 2; }
 
-template <int V, int G, int T, int U, int NT, bool UA, bool HOT = false>
+template <int V, int G, int T, int U, int NT, bool UA, bool HOT = false, int COLD = 0>
 __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     using vec = typename Vec<V>::type;
     constexpr int S = kWave / G;
@@ -219,6 +241,12 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     }
     const float *Bc = a.b_tile_stride ? a.B + (int64_t)ct * a.b_tile_stride : a.B;
     const uint32_t ldb = (uint32_t)a.ldb;
+    ColdPath cold{};
+    if constexpr (COLD != 0) {
+        cold.rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<float *>(Bc), 0, (uint32_t)a.b_bytes, 0x00020000);
+        cold.ldb_bytes = ldb * 4u;
+    }
+    const ColdPath *cp = COLD != 0 ? &cold : nullptr;
 
     int *lcol = s_raw + wv * smem_ints_per_wave();
     float *lval = reinterpret_cast<float *>(lcol + kStageMax);
@@ -231,8 +259,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
     if (b < (uint32_t)a.nb_items) {
         // ---- piece of a long row: 4 wavefronts, LDS tree, then C or a partial row ----
         const int4 it = a.items[b];
-        row_accumulate<V, G, T, U, NTA, UA, HOT>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
-                                                 a.vals, Bc, ldb, colok[0], boff, a.hotmask);
+        row_accumulate<V, G, T, U, NTA, UA, HOT, COLD>(acc, lcol, lval, lane, grp, it.y + wv * kWave, it.z, kBlock, a.colidx,
+                                                       a.vals, Bc, ldb, colok[0], boff, a.hotmask, cp);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
 #pragma unroll
@@ -322,8 +350,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (idx >= a.n_wave_rows) return;
         const int row = a.wave_rows[idx];
         const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
-        row_accumulate<V, G, T, U, NTA, UA, HOT>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, ldb,
-                                                 colok[0], boff, a.hotmask);
+        row_accumulate<V, G, T, U, NTA, UA, HOT, COLD>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, ldb,
+                                                       colok[0], boff, a.hotmask, cp);
         reduce_groups<V, G, T>(acc);
         if (grp == 0) {
             float *dst = a.C + (int64_t)row * a.ldc;
@@ -403,7 +431,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         if (q1 - q0 > a.LW) continue;  // medium/long row: handled by another path
 #pragma unroll
         for (int t = 0; t < T; ++t) acc[t] = vzero<V>();
-        gather_fma<V, T, U, UA, HOT>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, ldb, colok[0], boff);
+        gather_fma<V, T, U, UA, HOT, COLD>(acc, lcol, lval, q0 - sbeg, q1 - sbeg, 1, Bc, ldb, colok[0], boff, cp);
         float *dst = a.C + (int64_t)(r0 + ri) * a.ldc;
 #pragma unroll
         for (int t = 0; t < T; ++t)
@@ -698,7 +726,11 @@ typedef void (*kernel_fn)(const ExecArgs);
     }
 
 static kernel_fn pick_fused(int V, int G, int T, int U, int NT, bool UA) { SCORCH_PICK(spmm_fused_kernel) }
-static kernel_fn pick_fused_hot(int G, int T) {
+static kernel_fn pick_fused_hot(int G, int T, int cold) {
+    // experiments with the cache policy of the cold rows: whole rows of 97..128 columns only
+    if (G == 32 && T == 1 && cold == 1) return spmm_fused_kernel<4, 32, 1, 8, 1, false, true, 1>;
+    if (G == 32 && T == 1 && cold == 2) return spmm_fused_kernel<4, 32, 1, 8, 1, false, true, 2>;
+    if (G == 32 && T == 1 && cold == 3) return spmm_fused_kernel<4, 32, 1, 8, 1, false, true, 3>;
     if (T == 2) return spmm_fused_kernel<4, 64, 2, 8, 1, false, true>;
     switch (G) {
         case 8: return spmm_fused_kernel<4, 8, 1, 8, 1, false, true>;
@@ -798,7 +830,8 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
             (plan->params.NT & 1)) {
             // hot/cold variant: rows of B outside the plan's hot set are read with the streaming policy
             a.hotmask = reinterpret_cast<const uint32_t *>(ws + plan->layout.off_hotmask);
-            fn = pick_fused_hot(mp.G, mp.T);
+            a.b_bytes = (int64_t)plan->k * ldb * 4;
+            fn = pick_fused_hot(mp.G, mp.T, a.b_bytes < (1ll << 32) ? plan->tuning.cold : 0);
         }
         hipLaunchKernelGGL(fn, dim3((uint32_t)grid), dim3(kBlock), 0, stream, a);
         hipError_t e = hipGetLastError();

@@ -38,6 +38,7 @@ struct PlanParams {
     int32_t SLICED; // >0: XCD-sliced execution with this many columns of B per slice (32, 64 or 128; see want_sliced)
     int32_t PACK;   // 1: sliced execution gathers from a slice-major copy of B made at every call
     int32_t PANEL;  // dense-ish sorted rows: stream B through LDS in k-panels (spmm_panel.hip); 1: 256-column tiles, 2: 512
+    int32_t PDIRECT; // panel kernel: 1 = fetch the panels from the caller's row-major B instead of a tile-major copy
     int32_t HOT;    // >0: budget in KB for the most referenced rows of B, which alone keep the default cache policy
 };
 
@@ -83,14 +84,16 @@ struct ExecArgs {
     int32_t act;            // epilogue: 0 identity, 1 ReLU
     const uint32_t *hotmask;  // one bit per column of A, set for the most referenced rows of B (hot/cold variants only)
     int32_t rows_per_wave;    // plan-free kernel only: consecutive rows taken by one wavefront
+    int64_t b_bytes;          // size of B in bytes (cache-policy experiments of the hot/cold variants only)
 };
 
 struct PanelArgs {
     const int32_t *rowptr;
     const int32_t *colidx;
     const float *vals;
-    const float *Bp;  // tile-major copy of B: tile t is a dense k x 256 block
+    const float *Bp;  // tile-major copy of B (tile t is a dense k x 256 or k x 512 block), or the caller's row-major B
     float *C;
+    int64_t ldb;      // row stride of Bp when it is the caller's B
     int64_t ldc;
     int32_t m, k, n;
     int32_t nrb;     // row blocks of 4*RW rows

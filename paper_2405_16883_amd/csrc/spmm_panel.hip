@@ -33,17 +33,33 @@ typedef float f4 __attribute__((ext_vector_type(4)));
 // fetched straight from global memory into LDS (global_load_lds_dwordx4: no registers, no ds_write) while the
 // wavefronts work on the current one, and one barrier per panel both publishes the fetched panel and retires
 // the one before it.  A workgroup covers 16*RW rows, so B crosses L2 -> LDS m/(16*RW) times.
-template <int Q, int KR>
-__device__ __forceinline__ void panel_fetch(const f4 *Bt, int k, int k0, f4 *sbuf, int wv, int lane) {
+template <int Q, int KR, bool DIRECT>
+__device__ __forceinline__ void panel_fetch(const f4 *Bt, int k, int k0, f4 *sbuf, int wv, int lane, int64_t row_quads,
+                                            int quads_left) {
     constexpr int kRowQuads = Q * (kPanelCols / 4);
-    // The panel is one contiguous range of the tile: KR * Q chunks of 1 KB, dealt to the 16 wavefronts; a chunk is
-    // half a row or a row of B, so it lies wholly inside or wholly outside the tile.  The wavefront-uniform parts
+    // The panel is KR * Q chunks of 1 KB (64 lanes x 16 bytes), dealt to the 16 wavefronts; a chunk is half a row or a
+    // row of B inside the tile, so it lies wholly inside or wholly outside the matrix.  The wavefront-uniform parts
     // (panel base, validity of a chunk) are kept in scalar registers; a lane adds only its 32-bit offset.
-    const f4 *panel = Bt + (int64_t)k0 * kRowQuads;
+    if constexpr (!DIRECT) {
+        // tile-major copy of B: the panel is one contiguous range
+        const f4 *panel = Bt + (int64_t)k0 * kRowQuads;
 #pragma unroll
-    for (int c = 0; c < KR * Q / 16; ++c) {
-        const int chunk = c * 16 + wv;
-        if (k0 + chunk / Q < k) __builtin_amdgcn_global_load_lds(panel + (uint32_t)(chunk * 64 + lane), sbuf + chunk * 64, 16, 0, 0);
+        for (int c = 0; c < KR * Q / 16; ++c) {
+            const int chunk = c * 16 + wv;
+            if (k0 + chunk / Q < k) __builtin_amdgcn_global_load_lds(panel + (uint32_t)(chunk * 64 + lane), sbuf + chunk * 64, 16, 0, 0);
+        }
+    } else {
+        // the caller's row-major B: Bt points at the tile's first column of row 0, rows are row_quads vectors apart, and
+        // only quads_left vectors of a row lie inside the matrix (ragged last tile: the lanes past the row's end load
+        // nothing, and what they leave in LDS only feeds columns that are never stored)
+#pragma unroll
+        for (int c = 0; c < KR * Q / 16; ++c) {
+            const int chunk = c * 16 + wv;
+            const int row = chunk / Q, half = chunk % Q;
+            if (k0 + row < k && half * 64 + lane < quads_left)
+                __builtin_amdgcn_global_load_lds(Bt + (int64_t)(k0 + row) * row_quads + (uint32_t)(half * 64 + lane),
+                                                 sbuf + chunk * 64, 16, 0, 0);
+        }
     }
 }
 
@@ -140,7 +156,7 @@ __device__ __forceinline__ void panel_compute(PanelRows<RW, kBatch, Q> &st, cons
     }
 }
 
-template <int RW, int kBatch, int Q, int KR>
+template <int RW, int kBatch, int Q, int KR, bool DIRECT>
 __global__ __launch_bounds__(16 * kWave) void spmm_panel_kernel(const PanelArgs a) {
     constexpr int WPB = 16;
     constexpr int kRowQuads = Q * (kPanelCols / 4);
@@ -155,10 +171,14 @@ __global__ __launch_bounds__(16 * kWave) void spmm_panel_kernel(const PanelArgs 
     uint32_t ct, rb;
     if (!tile_of_workgroup(a.xcd_slices, a.ntiles, (uint32_t)a.nrb, ct, rb)) return;
     const int c0 = (int)ct * (Q * kPanelCols) + lane * 4;
-    const f4 *Bt = reinterpret_cast<const f4 *>(a.Bp + (int64_t)ct * a.k * (Q * kPanelCols));
+    // tile-major copy: tile ct is a dense k x (256 Q) block; row-major B: the tile starts at column 256 Q ct of every row
+    const f4 *Bt = reinterpret_cast<const f4 *>(DIRECT ? a.Bp + (int64_t)ct * (Q * kPanelCols)
+                                                       : a.Bp + (int64_t)ct * a.k * (Q * kPanelCols));
+    const int64_t row_quads = a.ldb / 4;
+    const int quads_left = (a.n - (int)ct * (Q * kPanelCols)) / 4;
     const int64_t row_base = (int64_t)rb * (WPB * RW) + wv * RW;
 
-    panel_fetch<Q, KR>(Bt, a.k, 0, s_b0, wv, lane);
+    panel_fetch<Q, KR, DIRECT>(Bt, a.k, 0, s_b0, wv, lane, row_quads, quads_left);
     PanelRows<RW, kBatch, Q> st;
 #pragma unroll
     for (int r = 0; r < RW; ++r) {
@@ -182,11 +202,11 @@ __global__ __launch_bounds__(16 * kWave) void spmm_panel_kernel(const PanelArgs 
     for (int k0 = 0; k0 < a.k; k0 += 2 * kRows) {
         panel_publish();  // panel k0 has landed in s_b0; nobody reads s_b1 any more
         const bool odd = k0 + kRows < a.k;
-        if (odd) panel_fetch<Q, KR>(Bt, a.k, k0 + kRows, s_b1, wv, lane);
+        if (odd) panel_fetch<Q, KR, DIRECT>(Bt, a.k, k0 + kRows, s_b1, wv, lane, row_quads, quads_left);
         panel_compute<RW, kBatch, Q, KR>(st, s_b0, k0, lane, a.colidx, a.vals);
         if (odd) {
             panel_publish();  // panel k0 + kRows has landed in s_b1; nobody reads s_b0 any more
-            if (k0 + 2 * kRows < a.k) panel_fetch<Q, KR>(Bt, a.k, k0 + 2 * kRows, s_b0, wv, lane);
+            if (k0 + 2 * kRows < a.k) panel_fetch<Q, KR, DIRECT>(Bt, a.k, k0 + 2 * kRows, s_b0, wv, lane, row_quads, quads_left);
             panel_compute<RW, kBatch, Q, KR>(st, s_b1, k0 + kRows, lane, a.colidx, a.vals);
         }
     }
@@ -225,14 +245,22 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
     struct Shape { int RW, WPB, Q; };
     const Shape sh = variant == 2 ? Shape{4, 16, 2} : Shape{4, 16, 1};
     const int W = sh.Q * kPanelCols;
-    float *Bp = reinterpret_cast<float *>(plan->workspace + plan->layout.off_bpack);
-    scorch_status_t st = launch_pack_b(B, ldb, plan->k, plan->n, W, Bp, stream);
-    if (st != SCORCH_OK) return st;
+    // The panels are fetched either from a tile-major copy of B made here (one read and one write of B per call) or
+    // straight from the caller's row-major B (pack=0 in the tuning text; see want_panel for the measurements).
+    const bool direct = plan->params.PDIRECT != 0;
+    const float *Bsrc = B;
+    if (!direct) {
+        float *Bp = reinterpret_cast<float *>(plan->workspace + plan->layout.off_bpack);
+        scorch_status_t st = launch_pack_b(B, ldb, plan->k, plan->n, W, Bp, stream);
+        if (st != SCORCH_OK) return st;
+        Bsrc = Bp;
+    }
     PanelArgs a{};
     a.rowptr = rowptr;
     a.colidx = colidx;
     a.vals = vals;
-    a.Bp = Bp;
+    a.Bp = Bsrc;
+    a.ldb = ldb;
     a.C = C;
     a.ldc = ldc;
     a.m = plan->m;
@@ -249,8 +277,13 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
         return SCORCH_ERR_UNSUPPORTED;
     }
     const dim3 g((uint32_t)grid), b(sh.WPB * kWave);
-    if (variant == 2) hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 40>), g, b, 0, stream, a);
-    else hipLaunchKernelGGL((spmm_panel_kernel<4, 4, 1, 64>), g, b, 0, stream, a);
+    if (variant == 2) {
+        if (direct) hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 40, true>), g, b, 0, stream, a);
+        else hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 40, false>), g, b, 0, stream, a);
+    } else {
+        if (direct) hipLaunchKernelGGL((spmm_panel_kernel<4, 4, 1, 64, true>), g, b, 0, stream, a);
+        else hipLaunchKernelGGL((spmm_panel_kernel<4, 4, 1, 64, false>), g, b, 0, stream, a);
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return hip_fail(e, "launch spmm_panel_kernel");
     return SCORCH_OK;

@@ -10,7 +10,7 @@ namespace scorch {
 
 struct Tuning {
     int32_t bn = 0, alpha = 0, lw = 0, ch = 0, bch = 0, u = 0, nt = -1, sliced = -1, pack = -1, panel = -1, hot = -1,
-            sdblk = -1, fix = -1;
+            sdblk = -1, fix = -1, cold = 0;
 };
 
 // Unknown keys, items without '=', and values that are not decimal integers are skipped; a value is clamped to the
@@ -22,7 +22,7 @@ inline Tuning parse_tuning(const char *s) {
     static const Key keys[] = {{"bn", &Tuning::bn}, {"alpha", &Tuning::alpha}, {"lw", &Tuning::lw}, {"ch", &Tuning::ch},
                                {"bch", &Tuning::bch}, {"u", &Tuning::u}, {"nt", &Tuning::nt}, {"sliced", &Tuning::sliced},
                                {"pack", &Tuning::pack}, {"panel", &Tuning::panel}, {"hot", &Tuning::hot},
-                               {"sdblk", &Tuning::sdblk}, {"fix", &Tuning::fix}};
+                               {"sdblk", &Tuning::sdblk}, {"fix", &Tuning::fix}, {"cold", &Tuning::cold}};
     const char *p = s;
     while (*p) {
         const char *item = p;

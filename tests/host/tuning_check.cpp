@@ -21,12 +21,12 @@ using namespace scorch;
 int main() {
     Tuning d = parse_tuning(nullptr);
     EXPECT(d.bn == 0 && d.alpha == 0 && d.lw == 0 && d.ch == 0 && d.bch == 0 && d.u == 0);
-    EXPECT(d.nt == -1 && d.sliced == -1 && d.pack == -1 && d.panel == -1 && d.hot == -1 && d.sdblk == -1 && d.fix == -1);
+    EXPECT(d.nt == -1 && d.sliced == -1 && d.pack == -1 && d.panel == -1 && d.hot == -1 && d.sdblk == -1 && d.fix == -1 && d.cold == 0);
     Tuning e = parse_tuning("");
     EXPECT(e.bn == 0 && e.sdblk == -1);
-    Tuning t = parse_tuning("bn=64,alpha=2,lw=8,ch=32,bch=64,u=4,nt=0,sliced=64,pack=1,panel=2,hot=65536,sdblk=3,fix=1");
+    Tuning t = parse_tuning("bn=64,alpha=2,lw=8,ch=32,bch=64,u=4,nt=0,sliced=64,pack=1,panel=2,hot=65536,sdblk=3,fix=1,cold=2");
     EXPECT(t.bn == 64 && t.alpha == 2 && t.lw == 8 && t.ch == 32 && t.bch == 64 && t.u == 4 && t.nt == 0);
-    EXPECT(t.sliced == 64 && t.pack == 1 && t.panel == 2 && t.hot == 65536 && t.sdblk == 3 && t.fix == 1);
+    EXPECT(t.sliced == 64 && t.pack == 1 && t.panel == 2 && t.hot == 65536 && t.sdblk == 3 && t.fix == 1 && t.cold == 2);
     t = parse_tuning(" bn = 128 ,, lw=0,junk,=5,bnx=3,b=9,ch=12x,hot=-1,sdblk=+2,panel=,alpha=99999999999,u=8,");
     EXPECT(t.bn == 128 && t.lw == 0 && t.ch == 0 && t.hot == -1 && t.sdblk == 2 && t.panel == -1 && t.u == 8);
     EXPECT(t.alpha == 0x7fffffff);

@@ -7,7 +7,7 @@ import pytest
 import torch
 
 import paper_2405_16883_amd as sp
-from oracle import plan_oracle
+from oracle import hot_columns_oracle, plan_oracle
 from workloads import (csr_from_row_lengths, integer_valued, make_scaled_config, with_padding)
 
 from gpu_util import DeviceProblem, check_against_oracle, read_plan_arrays, tuning
@@ -118,6 +118,10 @@ def test_panel_kernel_forced(m, k, n, shape):
     lens[rng.integers(0, m, size=5)] = 0
     lens[0] = min(k, 700)  # a row whose 64-entry register window slides many times
     p = csr_from_row_lengths(lens, k, n, seed=m, duplicates=False)
+    with tuning(f"panel={shape},pack=1"):  # panels fetched from a tile-major copy of B made at every call
+        run_both(p, label=f"panel packed {m}x{k}x{n}")
+        run_both(integer_valued(p, seed=n + 1), exact=True, label=f"panel packed int {m}x{k}x{n}")
+        run_both(with_padding(p, n + 4), ldc=n + 12, label=f"panel packed padded {m}x{k}x{n}")
     with tuning(f"panel={shape}"):
         d = DeviceProblem(p)
         plan = d.make_plan()
@@ -306,30 +310,19 @@ def test_hot_column_marking_changes_cache_policy_only(budget_kb):
     with tuning(f"hot={budget_kb}"):
         plan = d.make_plan()
         info = plan.info()
-        deg = np.bincount(p.colidx, minlength=p.k)
-
-        def degree_bin(x):
-            if x <= 0:
-                return 0
-            e = int(x).bit_length() - 1
-            frac = (x >> (e - 4)) & 15 if e >= 4 else (x << (4 - e)) & 15
-            return e * 16 + frac + 1
-
-        bins = np.array([degree_bin(int(x)) for x in deg])
-        max_rows = max(1, budget_kb * 1024 // (((p.n * 4 + 127) // 128) * 128))
-        rows, entries = 0, 0
-        for b in range(bins.max(), 0, -1):
-            cnt = int((bins == b).sum())
-            if rows + cnt > max_rows:
-                break
-            rows += cnt
-            entries += int(deg[bins == b].sum())
+        rows, share = hot_columns_oracle(p.colidx, p.k, p.n, budget_kb)
         assert info.n_hot_columns == rows
-        assert abs(info.hot_share - entries / p.nnz) < 1e-6
+        assert abs(info.hot_share - share) < 1e-6
         out = d.run_planned(plan)
         assert np.array_equal(out, base)
         check_against_oracle(p, out, d.ldc, label=f"hot={budget_kb}")
         plan.destroy()
+    # the cold rows read with the other cache-policy bits (experiments; buffer loads): the same bits again
+    for cold in (1, 2, 3):
+        with tuning(f"hot={budget_kb},cold={cold}"):
+            plan = d.make_plan()
+            assert np.array_equal(d.run_planned(plan), base), f"cold={cold} changed the result"
+            plan.destroy()
 
 
 def test_runs_on_a_side_stream():

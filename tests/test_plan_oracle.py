@@ -103,3 +103,17 @@ def test_dcsr_rowptr_oracle_round_trip():
         assert np.array_equal(dcsr_rowptr_oracle(p.m, ids, pos), p.rowptr)
     assert dcsr_rowptr_oracle(5, np.array([1, 3]), np.array([0, 2, 3])).tolist() == [0, 0, 2, 2, 3, 3]
     assert dcsr_rowptr_oracle(3, np.zeros(0, np.int64), np.array([0])).tolist() == [0, 0, 0, 0]
+
+
+def test_hot_columns_rule_on_a_hand_worked_case():
+    """Column counts 5, 3, 3, 1, 0 (12 entries).  Rows of B of 512 bytes and a 1 KB budget hold two rows: the bin of the
+    count 5 (one column) is taken, the bin of the count 3 (two columns) would make three rows and is not; with 256-byte
+    rows the budget holds four rows and the bins of 5, 3 and 1 are all taken; whole bins only, so two columns that tie
+    are marked together or not at all."""
+    from oracle import hot_columns_oracle
+    colidx = np.array([0] * 5 + [1] * 3 + [2] * 3 + [3])
+    assert hot_columns_oracle(colidx, 5, 128, 1) == (1, 5 / 12)
+    assert hot_columns_oracle(colidx, 5, 64, 1) == (4, 1.0)
+    assert hot_columns_oracle(colidx, 5, 100, 1) == (1, 5 / 12)  # 400-byte rows occupy 512 bytes of cache lines
+    assert hot_columns_oracle(colidx, 5, 128, 2) == (4, 1.0)
+    assert hot_columns_oracle(np.zeros(0, np.int64), 3, 64, 1) == (0, 0.0)
