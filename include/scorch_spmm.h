@@ -181,6 +181,7 @@ scorch_status_t scorch_spmm_plan_destroy(scorch_spmm_plan_t *plan);
  *   win_row_start  int32[n_windows + 1]
  *   win_stage      int32[n_windows][2]         entries a window stages (see off_win_stage)
  *   wave_rows      int32[n_wave_rows]          ascending row ids
+ *   wave_span      int32[n_wave_rows][2]       their entry ranges (rowptr[row], rowptr[row + 1])
  *   items          int32[n_items][4]           (row, p_begin, p_end, partial slot or -1)
  *   split          int32[n_split_rows][4]      (row, first slot, pieces, 0)
  *   partials       float[n_partial_slots][partial_stride]
@@ -197,6 +198,7 @@ typedef struct scorch_spmm_plan_info {
     int32_t n_hot_columns; /* columns whose rows of B keep the default cache policy (0: no hot/cold split) */
     float hot_share;       /* share of the stored entries that point at those columns (beyond 2^24 entries:
                               of an evenly spread sample of 2^23..2^24 of them, which is what ranks the columns) */
+    uint64_t off_wave_span; /* int32[n_wave_rows][2]: entry range [p0, p1) of every wave row, in the order of wave_rows */
     uint64_t off_win_stage; /* int32[n_windows][2]: (first entry, number of entries) between the first and the last
                                short row of the window, capped at 320 entries; (0, -1) for a window without short rows */
 } scorch_spmm_plan_info_t;

@@ -12,7 +12,7 @@ with sorts, searches and Python loops, no parallel tricks:
                 first such row; there are NW = (nnz + ALPHA*m)//BN + 1 windows
   * win_stage   per window (first entry, number of entries) from the first to the last short row among its first
                 64 rows, the number capped at STAGE_MAX = 320; (0, -1) when it has no short row
-  * wave_rows   the class-1 row ids, ascending
+  * wave_rows   the class-1 row ids, ascending; wave_span their entry ranges (rowptr[i], rowptr[i+1])
   * items       for every class-2 row, ascending: its nnz range cut into pieces of at most BCH;
                 a row cut into more than one piece gets consecutive partial-sum slots
   * split       (row, first_slot, pieces) for every row with more than one piece, ascending
@@ -71,6 +71,7 @@ def plan_oracle(rowptr: np.ndarray, BN: int, ALPHA: int, LW: int, CH: int, BCH: 
         "win_row_start": win_row_start,
         "win_stage": win_stage,
         "wave_rows": wave_rows,
+        "wave_span": np.stack([rp[wave_rows], rp[wave_rows + 1]], axis=1).astype(np.int32).reshape(-1, 2),
         "items": np.array(items, dtype=np.int32).reshape(-1, 4),
         "split": np.array(split, dtype=np.int32).reshape(-1, 4),
         "n_slots": np.int64(slot),

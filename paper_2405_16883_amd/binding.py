@@ -45,7 +45,7 @@ class PlanInfo(ctypes.Structure):
         ("partial_stride", ctypes.c_int32), ("mode", ctypes.c_int32),
         ("off_win_row_start", ctypes.c_uint64), ("off_wave_rows", ctypes.c_uint64), ("off_items", ctypes.c_uint64),
         ("off_split", ctypes.c_uint64), ("off_partials", ctypes.c_uint64), ("workspace_bytes_used", ctypes.c_uint64),
-        ("n_hot_columns", ctypes.c_int32), ("hot_share", ctypes.c_float), ("off_win_stage", ctypes.c_uint64),
+        ("n_hot_columns", ctypes.c_int32), ("hot_share", ctypes.c_float), ("off_wave_span", ctypes.c_uint64), ("off_win_stage", ctypes.c_uint64),
     ]
 
 

@@ -32,7 +32,9 @@ struct SddmmArgs {
     int64_t ldb, ldct;
     int32_t m, d;
     const int32_t *win_row_start;
+    const int2 *win_stage;  // per window: (first staged entry, number of staged entries); y < 0: no short row
     const int32_t *wave_rows;
+    const int2 *wave_span;  // [p0, p1) of every wave row
     const int4 *items;
     int32_t n_windows, n_wave_rows, n_items;
     int32_t nb_items, nb_wave, nb_win;
@@ -277,9 +279,9 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
         const int idx = (int)(b - a.nb_items) * kWavesPerBlock + wv;
         if (idx >= a.n_wave_rows) return;
         const int row = a.wave_rows[idx];
+        const int2 span = a.wave_span[idx];  // the row's entry range, kept in the plan beside its id
         load_x<V, T, UA>(x, a.B + (int64_t)row * a.ldb, colok, coff, nmask);
-        sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, a.rowptr[row], a.rowptr[row + 1], kWave, a, Yc, colok,
-                                      coff, nmask);
+        sddmm_row<V, G, T, false, UA>(x, lcol, lval, lane, grp, lig, span.x, span.y, kWave, a, Yc, colok, coff, nmask);
         return;
     }
     // window of consecutive short rows: stage the window's entries once, one lane group per row
@@ -287,20 +289,14 @@ __global__ __launch_bounds__(kBlock) void sddmm_kernel(const SddmmArgs a) {
     if (w >= a.n_windows) return;
     const int r0 = a.win_row_start[w];
     const int r1 = a.win_row_start[w + 1];
+    // which entries the window stages (first to last short row) is known from the plan, so colidx/vals are requested
+    // together with the row pointers instead of after them
+    const int2 stg = a.win_stage[w];
+    if (stg.y <= 0) return;  // no short row, or only empty ones
     const int nr = min(r1 - r0, kWindowRowsMax);
-    if (nr <= 0) return;
+    const int sbeg = stg.x, cnt = stg.y;
     const int rpv = a.rowptr[r0 + min(lane, nr)];
     const int rlast = a.rowptr[r0 + nr];
-    int rnext = __shfl_down(rpv, 1, kWave);
-    if (lane == kWave - 1) rnext = rlast;
-    const bool is_short = lane < nr && (rnext - rpv) <= a.LW && rnext > rpv;
-    const unsigned long long bal = __ballot(is_short);
-    if (bal == 0ull) return;
-    const int first = __builtin_ctzll(bal);
-    const int last = 63 - __builtin_clzll(bal);
-    const int sbeg = __shfl(rpv, first, kWave);
-    const int send = __shfl(rnext, last, kWave);
-    const int cnt = min(send - sbeg, kStageMax);
     for (int e = lane; e < cnt; e += kWave) {
         lcol[e] = a.colidx[sbeg + e];
         lval[e] = a.vals[sbeg + e];
@@ -508,7 +504,9 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
     } else if (plan) {
         char *ws = plan->workspace;
         a.win_row_start = reinterpret_cast<const int32_t *>(ws + plan->layout.off_win);
+        a.win_stage = reinterpret_cast<const int2 *>(ws + plan->layout.off_stage);
         a.wave_rows = reinterpret_cast<const int32_t *>(ws + plan->layout.off_wave);
+        a.wave_span = reinterpret_cast<const int2 *>(ws + plan->layout.off_wave_span);
         a.items = reinterpret_cast<const int4 *>(ws + plan->layout.off_items);
         a.n_windows = (int32_t)plan->layout.n_windows;
         a.n_wave_rows = plan->n_wave;

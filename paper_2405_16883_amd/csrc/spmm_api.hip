@@ -279,6 +279,7 @@ scorch_status_t scorch_spmm_plan_info(const scorch_spmm_plan_t *plan, scorch_spm
     out->mode = plan->params.PANEL ? 2 : (plan->params.SLICED ? 1 : 0);
     out->off_win_row_start = plan->layout.off_win;
     out->off_win_stage = plan->layout.off_stage;
+    out->off_wave_span = plan->layout.off_wave_span;
     out->off_wave_rows = plan->layout.off_wave;
     out->off_items = plan->layout.off_items;
     out->off_split = plan->layout.off_split;

@@ -349,7 +349,8 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         const int idx = (int)(b - a.nb_items) * kWavesPerBlock + wv;
         if (idx >= a.n_wave_rows) return;
         const int row = a.wave_rows[idx];
-        const int p0 = a.rowptr[row], p1 = a.rowptr[row + 1];
+        const int2 span = a.wave_span[idx];  // the row's entry range, kept in the plan beside its id
+        const int p0 = span.x, p1 = span.y;
         row_accumulate<V, G, T, U, NTA, UA, HOT, COLD>(acc, lcol, lval, lane, grp, p0, p1, kWave, a.colidx, a.vals, Bc, ldb,
                                                        colok[0], boff, a.hotmask, cp);
         reduce_groups<V, G, T>(acc);
@@ -786,6 +787,7 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     a.win_row_start = reinterpret_cast<const int32_t *>(ws + plan->layout.off_win);
     a.win_stage = reinterpret_cast<const int2 *>(ws + plan->layout.off_stage);
     a.wave_rows = reinterpret_cast<const int32_t *>(ws + plan->layout.off_wave);
+    a.wave_span = reinterpret_cast<const int2 *>(ws + plan->layout.off_wave_span);
     a.items = reinterpret_cast<const int4 *>(ws + plan->layout.off_items);
     a.partials = reinterpret_cast<float *>(ws + plan->layout.off_partials);
     // Partial rows of split rows are added by a second, small launch.  Adding them inside the fused launch, by the piece

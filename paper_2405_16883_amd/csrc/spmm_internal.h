@@ -47,7 +47,7 @@ Tuning read_tuning_from_env();
 PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tuning &t);
 
 struct WorkspaceLayout {
-    uint64_t off_counts, off_totals, off_win, off_stage, off_wave, off_items, off_split, off_partials, off_tickets, off_bpack,
+    uint64_t off_counts, off_totals, off_win, off_stage, off_wave, off_wave_span, off_items, off_split, off_partials, off_tickets, off_bpack,
         off_coldeg, off_hotmask, off_degbins, total;
     int64_t ticket_tiles;  // arrival counters per split row: one for every column tile a launch may use
     int64_t n_windows, nblk;
@@ -68,6 +68,7 @@ struct ExecArgs {
     const int32_t *win_row_start;
     const int2 *win_stage;  // per window: (first staged entry, number of staged entries) of its short rows; y < 0: no short row
     const int32_t *wave_rows;
+    const int2 *wave_span;  // [p0, p1) of every wave row: spares the wavefront the row-pointer read
     const int4 *items;
     float *partials;
     int32_t *tickets;  // arrival counters of the split rows (nullptr: partial rows are added by the fix-up launch)

@@ -29,6 +29,7 @@ struct PlanArgs {
     int32_t *counts;  // [kQ][nblk], turned into exclusive offsets by the scan
     int32_t *totals;  // [kQ]
     int32_t *wave_rows;
+    int2 *wave_span;  // entry range [p0, p1) of every wave row, beside its id
     int4 *items;
     int4 *split;
     int64_t cap_wave, cap_items, cap_split;  // list capacities: writes beyond them are dropped
@@ -146,7 +147,10 @@ __global__ __launch_bounds__(kBlock) void plan_scatter_kernel(const PlanArgs a) 
     const int pos_slot = a.counts[3 * a.nblk + blockIdx.x] + block_exclusive_scan(rc.slots, total, s_wave);
     // The capacities hold for every valid rowptr; the guards only keep a malformed one in bounds
     // (the host then reports the overflow from the totals).
-    if (rc.wave && pos_wave < a.cap_wave) a.wave_rows[pos_wave] = (int)i;
+    if (rc.wave && pos_wave < a.cap_wave) {
+        a.wave_rows[pos_wave] = (int)i;
+        a.wave_span[pos_wave] = make_int2(p0, p1);
+    }
     for (int c = 0; c < rc.items && (int64_t)pos_item + c < a.cap_items; ++c) {
         const int b = p0 + c * a.BCH;
         a.items[pos_item + c] = make_int4((int)i, b, min(p1, b + a.BCH), rc.split ? pos_slot + c : -1);
@@ -507,6 +511,8 @@ WorkspaceLayout layout_workspace(int32_t m, int32_t k, int64_t nnz, int32_t n, c
     off = align_up(off + (uint64_t)L.n_windows * 8, 256);
     L.off_wave = off;
     off = align_up(off + (uint64_t)L.cap_wave * 4, 256);
+    L.off_wave_span = off;
+    off = align_up(off + (uint64_t)L.cap_wave * 8, 256);
     L.off_items = off;
     off = align_up(off + (uint64_t)L.cap_items * 16, 256);
     L.off_split = off;
@@ -564,6 +570,7 @@ scorch_status_t build_plan(scorch_spmm_plan_t *plan, const int32_t *rowptr, cons
         a.counts = reinterpret_cast<int32_t *>(ws + L.off_counts);
         a.totals = reinterpret_cast<int32_t *>(ws + L.off_totals);
         a.wave_rows = reinterpret_cast<int32_t *>(ws + L.off_wave);
+        a.wave_span = reinterpret_cast<int2 *>(ws + L.off_wave_span);
         a.items = reinterpret_cast<int4 *>(ws + L.off_items);
         a.split = reinterpret_cast<int4 *>(ws + L.off_split);
         a.cap_wave = L.cap_wave;

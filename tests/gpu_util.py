@@ -159,6 +159,7 @@ def read_plan_arrays(plan):
         "win_row_start": view(info.off_win_row_start, info.n_windows + 1).copy(),
         "win_stage": view(info.off_win_stage, info.n_windows, 2).copy(),
         "wave_rows": view(info.off_wave_rows, info.n_wave_rows).copy(),
+        "wave_span": view(info.off_wave_span, info.n_wave_rows, 2).copy(),
         "items": view(info.off_items, info.n_items, 4).copy(),
         "split": view(info.off_split, info.n_split_rows, 4).copy(),
     }

@@ -268,7 +268,7 @@ def test_plan_lists_match_the_plan_oracle_bit_for_bit(cfg, scale, tune):
         want = plan_oracle(p.rowptr, info.BN, info.ALPHA, info.LW, info.CH, info.BCH)
         assert info.nnz == p.nnz and info.n_short_rows == int(want["n_short"])
         assert info.n_partial_slots == int(want["n_slots"])
-        for key in ("win_row_start", "win_stage", "wave_rows", "items", "split"):
+        for key in ("win_row_start", "win_stage", "wave_rows", "wave_span", "items", "split"):
             assert got[key].shape == want[key].shape, key
             assert np.array_equal(got[key], want[key]), key
         plan.destroy()
@@ -282,7 +282,7 @@ def test_plan_edge_patterns_match_oracle():
             plan = d.make_plan()
             info, got = read_plan_arrays(plan)
             want = plan_oracle(p.rowptr, info.BN, info.ALPHA, info.LW, info.CH, info.BCH)
-            for key in ("win_row_start", "win_stage", "wave_rows", "items", "split"):
+            for key in ("win_row_start", "win_stage", "wave_rows", "wave_span", "items", "split"):
                 assert np.array_equal(got[key], want[key]), (key, lens[:4])
             plan.destroy()
 

@@ -38,6 +38,7 @@ def check_plan(rowptr, P, BN, ALPHA, LW, CH, BCH):
     np.add.at(covered, P["wave_rows"], 1)
     assert np.all((lens[P["wave_rows"]] > LW) & (lens[P["wave_rows"]] <= CH))
     assert np.all(np.diff(P["wave_rows"]) > 0)
+    assert np.array_equal(P["wave_span"], np.stack([rp[P["wave_rows"]], rp[P["wave_rows"] + 1]], axis=1))
     items = P["items"].astype(np.int64)
     seen_slots = []
     for row in np.unique(items[:, 0]) if len(items) else []:
