@@ -234,6 +234,7 @@ def measure_practical_peak(torch, flush_buf):
     lib.scorch_probe_stream_read.argtypes = [vp, sz, i32, vp, vp]
     lib.scorch_probe_copy.argtypes = [vp, vp, sz, vp]
     lib.scorch_probe_row_gather.argtypes = [vp, u32, u32, i32, i64, i32, vp, vp]
+    lib.scorch_probe_lds_read.argtypes = [i32, i32, vp, vp]
     dev = "cuda:0"
     stream = ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
     sink = torch.zeros(64, dtype=torch.float32, device=dev)
@@ -259,6 +260,9 @@ def measure_practical_peak(torch, flush_buf):
     pk["stream_read_2GiB"] = 2 * gib / ms / 1e6
     ms = best_ms(lambda: lib.scorch_probe_copy(flush_buf.data_ptr(), big.data_ptr(), gib, stream))
     pk["copy_1GiB_read_plus_write"] = 2 * gib / ms / 1e6
+    lds_blocks, lds_iters = 256 * 8, 4096
+    ms = best_ms(lambda: lib.scorch_probe_lds_read(lds_blocks, lds_iters, sink.data_ptr(), stream))
+    pk["lds_read_b128"] = lds_blocks * 1024 * lds_iters * 16 / ms / 1e6
     groups, iters = 65536, 256
     pk["row_gather"] = {}
     for row_floats in (64, 100, 128):
@@ -275,7 +279,7 @@ def measure_practical_peak(torch, flush_buf):
     return pk
 
 
-def practical_floor(p, bytes_min, uniq_cols, pk):
+def practical_floor(p, bytes_min, uniq_cols, pk, l2_hit_rate=None):
     """Time a kernel would need that streams A and C at the measured streaming-read rate and fetches one whole row of B
     per stored entry at the measured random-row-gather rate for rows of this width from a table of B's size (no reuse
     of a row between entries: what a graph without locality offers beyond its hub rows).  Returned with its inputs."""
@@ -287,8 +291,18 @@ def practical_floor(p, bytes_min, uniq_cols, pk):
     gather_gbs = pk["row_gather"][width][size]
     stream_bytes = bytes_min - uniq_cols * row_bytes
     t = stream_bytes / (pk["stream_read_2GiB"] * 1e9) + p.nnz * row_bytes / (gather_gbs * 1e9)
-    return {"seconds": t, "gather_rate_used": f"{width}/{size}", "gather_gbs": gather_gbs,
-            "gather_bytes": p.nnz * row_bytes, "streamed_bytes": stream_bytes}
+    out = {"seconds": t, "gather_rate_used": f"{width}/{size}", "gather_gbs": gather_gbs,
+           "gather_bytes": p.nnz * row_bytes, "streamed_bytes": stream_bytes}
+    if l2_hit_rate is not None and size != "table_2MB_fits_one_L2":
+        # the same with the share of L2 hits the counters report for this kernel (profiles/): hits at the rate measured
+        # for an L2-resident table, the rest at the rate for a table of B's size
+        h = float(l2_hit_rate)
+        g = p.nnz * row_bytes
+        t2 = (stream_bytes / (pk["stream_read_2GiB"] * 1e9) + g * h / (pk["row_gather"][width]["table_2MB_fits_one_L2"] * 1e9)
+              + g * (1.0 - h) / (gather_gbs * 1e9))
+        out["seconds_at_measured_l2_hit_rate"] = t2
+        out["l2_hit_rate_used"] = h
+    return out
 
 
 def cpu_baseline_and_check(res, torch, target_nnz=80_000_000):
@@ -390,7 +404,7 @@ def main():
     practical = None if args.no_practical else measure_practical_peak(torch, flush_buf)
     if practical is not None:
         g = practical["row_gather"]
-        log(f"[bench] practical peak: stream read {practical['stream_read_2GiB']:.0f} GB/s, copy {practical['copy_1GiB_read_plus_write']:.0f} GB/s; "
+        log(f"[bench] practical peak: stream read {practical['stream_read_2GiB']:.0f} GB/s, copy {practical['copy_1GiB_read_plus_write']:.0f} GB/s, LDS reads {practical['lds_read_b128']:.0f} GB/s; "
             + "; ".join(f"{w} gathers " + "/".join(f"{v:.0f}" for v in g[w].values()) for w in g) + " GB/s (L2 / memory-side cache / beyond)")
 
     def run_config(cfg, steps, warmup, cold_steps):
@@ -431,11 +445,13 @@ def main():
                              "mode": {0: "gather", 1: "xcd_sliced_gather", 2: "lds_panel"}[info.mode],
                              "hot_columns": info.n_hot_columns, "hot_share": round(float(info.hot_share), 4)}})
         out["mode"] = out["plan"]["mode"]
+        tr_ = traffic.get(CONFIG_NAMES[cfg])
         if practical is not None:
-            fl = practical_floor(p, bytes_min, count_unique_columns(p), practical)
+            fl = practical_floor(p, bytes_min, count_unique_columns(p), practical, (tr_ or {}).get("l2_hit_rate") if info.mode != 2 else None)
             out["practical_floor"] = fl
             out["frac_of_practical"] = fl["seconds"] / (out["event_ms_mean"] * 1e-3)
-        tr_ = traffic.get(CONFIG_NAMES[cfg])
+            if "seconds_at_measured_l2_hit_rate" in fl:
+                out["frac_of_practical_at_measured_l2_hit_rate"] = fl["seconds_at_measured_l2_hit_rate"] / (out["event_ms_mean"] * 1e-3)
         if tr_:
             out["traffic"] = tr_["total_bytes"]
         if info.mode == 2:
@@ -473,6 +489,9 @@ def main():
         # floor from the rates measured in this run (see practical_floor) over the measured time: above 1 means the
         # kernel beats a reuse-free gather of one row of B per entry, i.e. it already gets reuse out of the caches
         "frac_of_practical": head.get("frac_of_practical"),
+        # the same floor with L2 hits priced at the L2-resident gather rate, at the hit rate the committed counter run
+        # reports for this kernel: near 1 means the kernel delivers what the cache levels deliver at that hit rate
+        "frac_of_practical_at_measured_l2_hit_rate": head.get("frac_of_practical_at_measured_l2_hit_rate"),
         "practical_floor": head.get("practical_floor"),
     }
     cpu = None if args.no_cpu else cpu_baseline_and_check(res, torch)
@@ -511,7 +530,7 @@ def main():
             others[CONFIG_NAMES[cfg]] = {k: o[k] for k in ("nnz", "n", "bytes_min", "event_ms_mean", "event_ms_min", "gflops",
                                                            "gbs_min_traffic", "frac_hbm", "cold_event_ms_mean",
                                                            "cold_frac_hbm", "plan_ms", "plan_free_event_ms_mean") + tuple(x for x in ("sddmm", "widenings") if x in o)
-                                        + tuple(x for x in ("mode", "traffic", "alu_roofline", "frac_of_practical", "practical_floor") if x in o)
+                                        + tuple(x for x in ("mode", "traffic", "alu_roofline", "frac_of_practical", "frac_of_practical_at_measured_l2_hit_rate", "practical_floor") if x in o)
                                         + (("graph_replay_ms_per_step",) if "graph_replay_ms_per_step" in o else ())}
             del r
 

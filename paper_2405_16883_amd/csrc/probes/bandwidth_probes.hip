@@ -6,6 +6,7 @@
 // benchmark's timed steps:
 //   stream read   every lane reads consecutive 16-byte vectors of a large buffer
 //   copy          the same with a streaming store of what was read
+//   LDS read      every lane of a 1024-thread workgroup reads 16-byte vectors out of LDS (what bounds the panel kernel)
 //   row gather    a group of lanes reads one whole row (256, 400 or 512 bytes) of a table at a pseudo-random row index,
 //                 U rows in flight per group -- the access pattern of C_i += A_ij * B_j with random j (the SpMM of the
 //                 paper, Section 4.2, on a graph without locality) -- from tables that fit one die's L2, that fit the
@@ -70,6 +71,28 @@ __global__ __launch_bounds__(kBlock) void probe_gather_kernel(const float *__res
     sink_store(sink, acc);
 }
 
+// every wavefront of a 1024-thread workgroup reads 16-byte vectors from a 64 KB LDS array, consecutive lanes consecutive
+// vectors (the pattern of the panel kernel's reads), 8 reads in flight per lane
+__global__ __launch_bounds__(1024) void probe_lds_kernel(int iters, float *sink) {
+    __shared__ f4 s_buf[4096];
+    for (int i = threadIdx.x; i < 4096; i += 1024) s_buf[i] = f4{(float)i, 1.f, 2.f, 3.f};
+    __syncthreads();
+    f4 acc = {0.f, 0.f, 0.f, 0.f};
+    const int lane = threadIdx.x & 63;
+    int row = (threadIdx.x >> 6) * 7;
+    for (int it = 0; it < iters; it += 8) {
+        f4 x[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            x[u] = s_buf[((row + u * 5) & 63) * 64 + lane];
+        }
+        row += 41;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += x[u];
+    }
+    sink_store(sink, acc);
+}
+
 }  // namespace
 
 extern "C" {
@@ -100,6 +123,14 @@ int scorch_probe_row_gather(const float *table, uint32_t rows, uint32_t ld, int 
         return -1;
     hipLaunchKernelGGL(probe_gather_kernel, dim3((uint32_t)(groups / 8)), dim3(kBlock), 0, static_cast<hipStream_t>(stream),
                        table, rows, ld, row_floats / 4, iters, sink);
+    return hipGetLastError() == hipSuccess ? 0 : -4;
+}
+
+// `blocks` workgroups of 1024 threads each read `iters` (multiple of 8) 16-byte vectors per thread from LDS.  Useful
+// bytes = blocks * 1024 * iters * 16.
+int scorch_probe_lds_read(int blocks, int iters, float *sink, void *stream) {
+    if (!sink || blocks <= 0 || iters <= 0 || iters % 8) return -1;
+    hipLaunchKernelGGL(probe_lds_kernel, dim3((uint32_t)blocks), dim3(1024), 0, static_cast<hipStream_t>(stream), iters, sink);
     return hipGetLastError() == hipSuccess ? 0 : -4;
 }
 
