@@ -57,7 +57,9 @@ typedef struct scorch_spmm_plan_s scorch_spmm_plan_t; /* small host-side handle 
  * Plan-free SpMM: C = A.B in natural row order.  A wavefront takes a short run of consecutive rows
  * (up to 4, up to 16 for small n), walks the short ones (up to 32 entries) side by side and streams the longer ones; the
  * four wavefronts of a workgroup work together on rows with more than 2048 entries (more than 256
- * where such rows are rare).  Always available and correct for any valid input; no load balancing
+ * where such rows are rare).  With B of 8 MB or more and n a multiple of 64 (128) the columns are walked in slices of
+ * 64 (128) that are dealt over the accelerator dies, so that each die gathers from a part of B its L2 can keep.
+ * Always available and correct for any valid input; no load balancing
  * beyond that, so a row with very many entries still runs on a single workgroup.  (Definition: see
  * the top of this file.)
  */

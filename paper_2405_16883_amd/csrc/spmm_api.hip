@@ -61,7 +61,7 @@ scorch_status_t scorch_spmm_csr(int32_t m, int32_t k, int32_t n, const int32_t *
                                 void *stream) {
     scorch_status_t st = check_operands(m, k, n, rowptr, colidx, vals, B, ldb, C, ldc);
     if (st != SCORCH_OK || m == 0 || n == 0) return st;
-    return launch_natural(m, n, rowptr, colidx, vals, B, ldb, C, ldc, static_cast<hipStream_t>(stream));
+    return launch_natural(m, k, n, rowptr, colidx, vals, B, ldb, C, ldc, static_cast<hipStream_t>(stream));
 }
 
 scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n, int64_t nnz, size_t *bytes_out) {

@@ -471,8 +471,8 @@ __global__ __launch_bounds__(kBlock) void spmm_natural_kernel(const ExecArgs a) 
     const int grp = lane / G;
     const int lig = lane % G;
     const uint32_t per_tile = (uint32_t)a.nb_wave;
-    const uint32_t ct = blockIdx.x / per_tile;
-    const uint32_t b = blockIdx.x - ct * per_tile;
+    uint32_t ct, b;
+    if (!tile_of_workgroup(a.xcd_slices, a.ncoltiles, per_tile, ct, b)) return;  // the same for the whole workgroup
     const int NR = a.rows_per_wave;
     const int64_t r0 = ((int64_t)b * kWavesPerBlock + wv) * NR;
     const int nr = (int)max((int64_t)0, min((int64_t)NR, (int64_t)a.m - r0));
@@ -857,10 +857,20 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     return SCORCH_OK;
 }
 
-scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
+scorch_status_t launch_natural(int32_t m, int32_t k, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                hipStream_t stream) {
-    const Mapping mp = pick_mapping(n, B, ldb, C, ldc, 0);
+    // Column slices dealt over the XCDs (tile_of_workgroup) need no plan, only the shape: with B of 8 MB or more every
+    // XCD walks all rows for one slice of columns at a time, so that the part of B it gathers from is 1/s of B.  Measured
+    // on the plan-free call: uniform 1 % pattern, n = 128: 90 -> 69 us with 64-column slices; pruned 4096 x 16384 weight,
+    // n = 2048: 5.03 -> 2.26 ms with 128-column slices (64 columns: 3.0 ms, 32: 4.3 ms, 256: 4.2 ms); mid-size graph,
+    // n = 128: 168 -> 166 us.  A ragged last slice costs more than it gains, hence the multiples.
+    int slice_cols = 0;
+    if ((int64_t)k * n * 4 >= (8ll << 20)) {
+        if (n >= 256 && n % 128 == 0) slice_cols = 128;
+        else if (n >= 128 && n % 64 == 0) slice_cols = 64;
+    }
+    const Mapping mp = pick_mapping(n, B, ldb, C, ldc, slice_cols);
     ExecArgs a{};
     a.rowptr = rowptr;
     a.colidx = colidx;
@@ -871,6 +881,7 @@ scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, cons
     a.ldc = ldc;
     a.m = m;
     a.n = n;
+    a.xcd_slices = mp.xcd_slices;
     // rows per wavefront: 4 once that leaves a workgroup for every compute unit (measured: 1, 2, 4, 8, 16 rows on the
     // five benchmark workloads; 4 is within 1 % of the best of each that has 16 384 rows or more)
     // (narrow lane groups, i.e. many groups per wavefront: up to one row per group)
@@ -878,7 +889,7 @@ scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, cons
     a.rows_per_wave = (int32_t)std::min<int64_t>(rows_cap, std::max<int64_t>(1, m / 4096));
     a.nb_wave = (int32_t)ceil_div64(m, (int64_t)kWavesPerBlock * a.rows_per_wave);
     a.ncoltiles = mp.ncoltiles;
-    const int64_t grid = (int64_t)a.nb_wave * mp.ncoltiles;
+    const int64_t grid = grid_size(mp, a.nb_wave);
     if (grid > 0x7fffffffLL) {
         set_error("launch grid of %lld workgroups exceeds the HIP limit", (long long)grid);
         return SCORCH_ERR_UNSUPPORTED;

@@ -167,7 +167,7 @@ scorch_status_t launch_sddmm(const scorch_spmm_plan_t *plan, int32_t m, int32_t 
                              const int32_t *colidx, const float *vals, const float *B, int64_t ldb, const float *Ct,
                              int64_t ldct, float *out, hipStream_t stream);
 
-scorch_status_t launch_natural(int32_t m, int32_t n, const int32_t *rowptr, const int32_t *colidx,
+scorch_status_t launch_natural(int32_t m, int32_t k, int32_t n, const int32_t *rowptr, const int32_t *colidx,
                                const float *vals, const float *B, int64_t ldb, float *C, int64_t ldc,
                                hipStream_t stream);
 

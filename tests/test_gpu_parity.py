@@ -375,3 +375,17 @@ def test_split_rows_added_inside_the_launch_match_the_second_launch_bit_for_bit(
                 assert np.array_equal(got, want), f"fix={fix} differs from the fix-up launch at repetition {rep} (n={n}, {tune})"
             plan.destroy()
             run_both(integer_valued(p, seed=n), exact=True, label=f"fix={fix} int n={n} [{tune}]")
+
+
+@pytest.mark.parametrize("k,n", [(16384, 128), (8192, 256), (2048, 1024), (1024, 2176), (4100, 640), (33000, 64), (16384, 192)])
+def test_plan_free_call_with_column_slices_over_the_dies(k, n):
+    """Shapes whose B reaches 8 MB: the plan-free call deals 64- or 128-column slices over the XCDs (2 to 17 slices,
+    i.e. whole rounds of 8 plus shared rounds); shapes just outside the rule (n = 64, n not a multiple) keep whole rows."""
+    rng = np.random.default_rng(n + k)
+    lens = np.concatenate([rng.integers(0, 70, size=300), [2500, 0, 300, 700, 64, 33, 32, 1, 0]])
+    p = csr_from_row_lengths(lens, k, n, seed=n, duplicates=True)
+    d = DeviceProblem(p)
+    check_against_oracle(p, d.run_natural(), d.ldc, label=f"plan-free sliced k={k} n={n}")
+    q = integer_valued(p, seed=k)
+    d = DeviceProblem(q, ldc=n + 4)
+    check_against_oracle(q, d.run_natural(), d.ldc, exact=True, label=f"plan-free sliced int k={k} n={n}")
