@@ -243,7 +243,7 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
     // 64 rows per workgroup and 128 or 160 KB of LDS, i.e. one workgroup and four wavefronts per SIMD on a CU.
     const int variant = plan->params.PANEL;
     struct Shape { int RW, WPB, Q; };
-    const Shape sh = variant == 2 ? Shape{4, 16, 2} : Shape{4, 16, 1};
+    const Shape sh = variant == 3 ? Shape{4, 16, 4} : (variant == 2 ? Shape{4, 16, 2} : Shape{4, 16, 1});
     const int W = sh.Q * kPanelCols;
     // The panels are fetched either from a tile-major copy of B made here (one read and one write of B per call) or
     // straight from the caller's row-major B (pack=0 in the tuning text; see want_panel for the measurements).
@@ -277,7 +277,10 @@ scorch_status_t launch_panel(const scorch_spmm_plan_t *plan, const int32_t *rowp
         return SCORCH_ERR_UNSUPPORTED;
     }
     const dim3 g((uint32_t)grid), b(sh.WPB * kWave);
-    if (variant == 2) {
+    if (variant == 3) {
+        // experiment (panel=3 in the tuning text, direct fetch only): 1024-column tiles, 20-row panels
+        hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 4, 20, true>), g, b, 0, stream, a);
+    } else if (variant == 2) {
         if (direct) hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 40, true>), g, b, 0, stream, a);
         else hipLaunchKernelGGL((spmm_panel_kernel<4, 2, 2, 40, false>), g, b, 0, stream, a);
     } else {

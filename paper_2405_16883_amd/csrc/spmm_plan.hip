@@ -448,12 +448,12 @@ PlanParams choose_params(int32_t m, int32_t k, int64_t nnz, int32_t n, const Tun
     p.PACK = (p.SLICED == kSliceCols && n > 128) ? 1 : 0;
     if (t.pack >= 0) p.PACK = (p.SLICED == kSliceCols && t.pack != 0) ? 1 : 0;
     p.PANEL = want_panel(m, k, nnz, n);
-    if (t.panel >= 0) p.PANEL = (t.panel > 0 && n % 4 == 0 && k > 0) ? t.panel : 0;
+    if (t.panel >= 0) p.PANEL = (t.panel > 0 && t.panel <= 3 && n % 4 == 0 && k > 0) ? t.panel : 0;
     // The panel kernel fetches its panels straight from the caller's row-major B (pruned-FFN workload, row stride 8 KB:
     // 1.10 against 1.13 ms with a tile-major copy made at every call, which costs one read and one write of B; the
     // workgroups of a tile column walk the same panels at the same time, so only a few panels per die have to stay in
     // L2 and the set conflicts of a power-of-two stride do not matter); pack=1 brings the copy back.
-    p.PDIRECT = (p.PANEL && t.pack != 1) ? 1 : 0;
+    p.PDIRECT = (p.PANEL && (t.pack != 1 || p.PANEL == 3)) ? 1 : 0;
     // Enough independent wavefront tasks to fill 256 CUs several times over, but pieces long
     // enough that the per-piece overhead stays small.
     const int64_t coltiles = p.SLICED ? (n + p.SLICED - 1) / p.SLICED : std::max<int64_t>(1, (n + 511) / 512);

@@ -108,7 +108,7 @@ def test_xcd_sliced_column_mapping(n):
             run_both(with_padding(p, n + 4), ldc=n + 8, label=f"sliced n={n} padded [{tune}]")
 
 
-@pytest.mark.parametrize("shape", [1, 2])
+@pytest.mark.parametrize("shape", [1, 2, 3])
 @pytest.mark.parametrize("m,k,n", [(64, 64, 256), (130, 200, 128), (515, 1000, 512), (300, 77, 260), (257, 4100, 1028),
                                    (1000, 333, 2048)])
 def test_panel_kernel_forced(m, k, n, shape):
@@ -140,7 +140,7 @@ def test_panel_kernel_forced(m, k, n, shape):
         plan.destroy()
 
 
-@pytest.mark.parametrize("shape", [1, 2])
+@pytest.mark.parametrize("shape", [1, 2, 3])
 @pytest.mark.parametrize("k", [1, 31, 32, 33, 39, 40, 41, 64, 65, 80, 81, 200])
 def test_panel_kernel_fully_dense_rows(k, shape):
     """Every row stores all k columns: each panel takes a whole 32- or 64-entry stretch of a row's register window,
