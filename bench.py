@@ -226,9 +226,10 @@ def measure_practical_peak(torch, flush_buf):
     The probe kernels live in a library of their own (paper_2405_16883_amd/csrc/probes), not in the product."""
     import ctypes
 
-    from paper_2405_16883_amd.build import PROBES_LIB_PATH
+    from paper_2405_16883_amd.build import PROBES_LIB_PATH, build_probes
     if not os.path.exists(PROBES_LIB_PATH):
-        raise FileNotFoundError(f"{PROBES_LIB_PATH} is missing: build it with __graft_entry__.build()")
+        log(f"[bench] {PROBES_LIB_PATH} is missing: building the bandwidth probes")
+        build_probes()
     lib = ctypes.CDLL(PROBES_LIB_PATH)
     vp, i32, i64, u32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_uint32, ctypes.c_size_t
     lib.scorch_probe_stream_read.argtypes = [vp, sz, i32, vp, vp]
@@ -401,7 +402,12 @@ def main():
     def flush():
         flush_buf.add_(1.0)
 
-    practical = None if args.no_practical else measure_practical_peak(torch, flush_buf)
+    practical = None
+    if not args.no_practical:
+        try:
+            practical = measure_practical_peak(torch, flush_buf)
+        except Exception as e:  # the probes are benchmark infrastructure: without them the line lacks practical_peak, nothing else
+            log(f"[bench] bandwidth probes unavailable ({e}); practical_peak is left out")
     if practical is not None:
         g = practical["row_gather"]
         log(f"[bench] practical peak: stream read {practical['stream_read_2GiB']:.0f} GB/s, copy {practical['copy_1GiB_read_plus_write']:.0f} GB/s, LDS reads {practical['lds_read_b128']:.0f} GB/s; "
