@@ -103,7 +103,7 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>,sdblk=..,fix=.."
  * overrides the built-in parameter choice (for experiments; sliced = 0, 1 (= 32), 32, 64 or 128 columns of B per
  * accelerator-die slice, panel = 0, 1 or 2; sdblk = blocks of columns of A per accelerator die in the planned
- * SDDMM, 0 = row-wise kernel; fix = 1 or 2: partial rows are added inside the fused launch, by the piece that finishes last, instead
+ * SDDMM, 0 = row-wise kernel; fix = 1: partial rows are added inside the fused launch, by the piece that finishes last, instead
  * of by a second launch).
  * The variable is read when a plan is made (and by scorch_spmm_plan_workspace_bytes), never by an execution call.
  */

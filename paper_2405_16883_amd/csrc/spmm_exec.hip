@@ -290,17 +290,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
                 // a partial row gets its epilogue after the pieces are added
                 if (it.w < 0) r = apply_epilogue<V>(r, a.bias ? a.bias + coff[t] : nullptr, a.act);
                 if (it.w < 0) vstore<V, NTC, UA>(dst + coff[t], r);
-                else if (a.fold == 2) {
-                    // experiment: every float of the partial row as a device-scope atomic store (written through this
-                    // die's L2), so that no L2 write-back is needed before the ticket
-#pragma unroll
-                    for (int i = 0; i < V; ++i) {
-                        float x;
-                        if constexpr (V == 1) x = r;
-                        else x = r[i];
-                        __hip_atomic_store(dst + coff[t] + i, x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    }
-                } else vstore<V, false, UA>(dst + coff[t], r);
+                else vstore<V, false, UA>(dst + coff[t], r);
             }
         }
         if (it.w < 0 || a.tickets == nullptr) return;  // whole row done, or the fix-up launch adds the partial rows
@@ -314,8 +304,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         const int pieces = (row_p1 - row_p0 + a.BCH - 1) / a.BCH;
         const int first = it.w - piece;
         if (wv == 0) {
-            if (a.fold == 2) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // experiment: the written-through stores have completed
-            else __threadfence();  // release: this wavefront's stores of the partial row, device-wide
+            __threadfence();  // release: this wavefront's stores of the partial row, device-wide
             if (lane == 0) {
                 int32_t *tk = a.tickets + ((int64_t)first * a.ncoltiles + ct);
                 const int old = atomicAdd(tk, 1);
@@ -326,7 +315,7 @@ __global__ __launch_bounds__(kBlock) void spmm_fused_kernel(const ExecArgs a) {
         }
         __syncthreads();
         if (!s_flag) return;
-        if (a.fold != 2) __threadfence();  // acquire: the other pieces' partial rows
+        __threadfence();  // acquire: the other pieces' partial rows
         {
             const float *src = a.partials + (int64_t)first * a.partial_stride;
             float *dst = a.C + (int64_t)it.x * a.ldc;
@@ -791,14 +780,13 @@ scorch_status_t launch_planned(const scorch_spmm_plan_t *plan, const int32_t *ro
     a.items = reinterpret_cast<const int4 *>(ws + plan->layout.off_items);
     a.partials = reinterpret_cast<float *>(ws + plan->layout.off_partials);
     // Partial rows of split rows are added by a second, small launch.  Adding them inside the fused launch, by the piece
-    // that arrives last, is built and tested but off by default (fix=1 or fix=2 in the tuning text turns it on): with
-    // proper device-scope release/acquire fences every piece makes its die write back and invalidate its L2, which
-    // cost 90 us on the mid-size graph workload (213 against 123 us); with written-through atomic stores instead of
-    // fences (fix=2) it saves 3.5 us, but then the order between the partial row and the ticket rests on the completion
-    // of written-through stores, which the language-level memory model does not promise.
+    // that arrives last, is built and tested but off by default (fix=1 in the tuning text turns it on): with proper
+    // device-scope release/acquire fences every piece makes its die write back and invalidate its L2, which cost 90 us
+    // on the mid-size graph workload (213 against 123 us).  A variant with written-through atomic stores instead of
+    // fences saved 3.5 us there, but the order between the partial row and the ticket then rests on when a
+    // written-through store counts as complete, which the language-level memory model does not promise: not kept.
     const bool fold = plan->n_split > 0 && plan->tuning.fix > 0;
     a.tickets = fold ? reinterpret_cast<int32_t *>(ws + plan->layout.off_tickets) : nullptr;
-    a.fold = fold ? (plan->tuning.fix == 2 ? 2 : 1) : 0;
     a.BCH = plan->params.BCH;
     a.n_windows = (int32_t)plan->layout.n_windows;
     a.n_wave_rows = plan->n_wave;

@@ -73,7 +73,6 @@ struct ExecArgs {
     float *partials;
     int32_t *tickets;  // arrival counters of the split rows (nullptr: partial rows are added by the fix-up launch)
     int32_t BCH;       // entries per piece of a long row
-    int32_t fold;      // 0: fix-up launch; 1: last piece adds the partial rows (fences); 2: the same with written-through atomic stores
     int32_t n_windows, n_wave_rows, n_items;
     int32_t nb_items, nb_wave, nb_win;  // workgroups per path, per column tile
     int32_t partial_stride;

@@ -353,7 +353,7 @@ def test_sparse_activation_times_dense_weight_shape(k, density):
                                     (256, "sliced=64,ch=64,bch=96"), (3, "ch=64,bch=64"), (64, "hot=4,ch=64,bch=64")])
 def test_split_rows_added_inside_the_launch_match_the_second_launch_bit_for_bit(n, tune):
     """Rows cut into many pieces (up to 150 per row, several column tiles or XCD slices).  Default: a second launch
-    adds the partial rows.  fix=1 / fix=2: the piece that arrives last adds them, in piece order, so the result equals
+    adds the partial rows.  fix=1: the piece that arrives last adds them, in piece order, so the result equals
     that of the second launch bit for bit at every repetition (the arrival order changes from run to run, the sum
     must not), and the arrival counters are back at zero after every launch (else the next one would go wrong)."""
     rng = np.random.default_rng(n)
@@ -367,7 +367,7 @@ def test_split_rows_added_inside_the_launch_match_the_second_launch_bit_for_bit(
         want = d.run_planned(plan).copy()
         plan.destroy()
     check_against_oracle(p, want, d.ldc, label=f"two launches n={n} [{tune}]")
-    for fix in (1, 2):
+    for fix in (1,):
         with tuning(tune + f",fix={fix}"):
             plan = d.make_plan()
             for rep in range(12):
