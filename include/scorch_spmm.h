@@ -100,11 +100,11 @@ scorch_status_t scorch_spmm_plan_workspace_bytes(int32_t m, int32_t k, int32_t n
  * each column occurs and marks the most referenced columns (up to 64 MB of rows of B) as hot; execution then
  * reads only those rows of B with the default cache policy and the others with the streaming policy.
  * This changes no result bit.
- * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>,sdblk=..,fix=.."
+ * Optional environment variable SCORCH_SPMM_TUNE="bn=..,alpha=..,lw=..,ch=..,bch=..,u=..,nt=..,sliced=..,pack=..,panel=..,hot=<KB>,sdblk=..,fix=..,cold=.."
  * overrides the built-in parameter choice (for experiments; sliced = 0, 1 (= 32), 32, 64 or 128 columns of B per
  * accelerator-die slice, panel = 0, 1 or 2; sdblk = blocks of columns of A per accelerator die in the planned
  * SDDMM, 0 = row-wise kernel; fix = 1: partial rows are added inside the fused launch, by the piece that finishes last, instead
- * of by a second launch).
+ * of by a second launch; cold = 1, 2, 3: cache-policy bits of the loads of the rows of B outside the hot set).
  * The variable is read when a plan is made (and by scorch_spmm_plan_workspace_bytes), never by an execution call.
  */
 scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
@@ -120,8 +120,8 @@ scorch_status_t scorch_spmm_plan(int32_t m, int32_t k, int32_t n,
  * leave partial rows in the workspace, which are added in piece order); for wide
  * B with few rows a pre-pass first copies B into column-slice-major order so that each accelerator
  * die keeps its slice of B in its own L2; matrices with a few percent of their entries stored and
- * strictly increasing columns in every row go to a kernel that streams that copy of B through LDS
- * instead of gathering.
+ * strictly increasing columns in every row go to a kernel that streams B through LDS, panel by panel,
+ * instead of gathering (straight from the caller's B; pack=1 in the tuning text: from a tile-major copy).
  * Never waits, never allocates.  The partial rows and the copy of B live in the plan workspace, so
  * two executions of one plan must not overlap in time (same stream, or synchronise).
  */
