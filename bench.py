@@ -222,7 +222,8 @@ def time_graph_replay(res, torch, sp, steps_per_graph=20, replays=10):
 def measure_practical_peak(torch, flush_buf):
     """What this chip delivers, measured now, on the launch stream, to the access patterns an SpMM consists of:
     a streaming read, a copy, and random gathers of whole 256/400/512-byte rows from tables that fit one die's L2 (2 MB),
-    that fit the 256 MB memory-side cache (96 MB) and that exceed both (2 GiB).  GB/s of useful bytes, best of 3 launches.
+    that are two and four times one L2 (8 and 16 MB: about half and a quarter of the gathers hit L2, the mix a graph
+    workload sees), that fit the 256 MB memory-side cache (96 MB) and that exceed both (2 GiB).  GB/s of useful bytes, best of 3 launches.
     The probe kernels live in a library of their own (paper_2405_16883_amd/csrc/probes), not in the product."""
     import ctypes
 
@@ -268,8 +269,9 @@ def measure_practical_peak(torch, flush_buf):
     pk["row_gather"] = {}
     for row_floats in (64, 100, 128):
         row = {}
-        for label, table_bytes in (("table_2MB_fits_one_L2", 2 << 20), ("table_96MB_fits_memory_side_cache", 96 << 20),
-                                   ("table_2GiB_beyond_both", 2 * gib)):
+        for label, table_bytes in (("table_2MB_fits_one_L2", 2 << 20), ("table_8MB_twice_one_L2", 8 << 20),
+                                   ("table_16MB_four_times_one_L2", 16 << 20),
+                                   ("table_96MB_fits_memory_side_cache", 96 << 20), ("table_2GiB_beyond_both", 2 * gib)):
             rows = table_bytes // (row_floats * 4)
             ms = best_ms(lambda: lib.scorch_probe_row_gather(big.data_ptr(), rows, row_floats, row_floats, groups, iters,
                                                              sink.data_ptr(), stream))
@@ -295,13 +297,29 @@ def practical_floor(p, bytes_min, uniq_cols, pk, l2_hit_rate=None):
     out = {"seconds": t, "gather_rate_used": f"{width}/{size}", "gather_gbs": gather_gbs,
            "gather_bytes": p.nnz * row_bytes, "streamed_bytes": stream_bytes}
     if l2_hit_rate is not None and size != "table_2MB_fits_one_L2":
-        # the same with the share of L2 hits the counters report for this kernel (profiles/): hits at the rate measured
-        # for an L2-resident table, the rest at the rate for a table of B's size
+        # The same at the share of L2 hits the counters report for this kernel (profiles/).  B inside the memory-side
+        # cache: the gather rate is read off the probe's own mixes (tables of 1, 2, 4 and 24 times one die's L2, i.e.
+        # about 100, 50, 25 and 4 % of L2 hits, misses served by the memory-side cache), linearly between the points.
+        # B beyond it: no probe table mixes L2 hits with HBM-served misses, so hits are priced at the L2-resident rate
+        # and misses at the beyond-both rate, one after the other (a model, pessimistic where the two overlap).
         h = float(l2_hit_rate)
         g = p.nnz * row_bytes
-        t2 = (stream_bytes / (pk["stream_read_2GiB"] * 1e9) + g * h / (pk["row_gather"][width]["table_2MB_fits_one_L2"] * 1e9)
-              + g * (1.0 - h) / (gather_gbs * 1e9))
-        out["seconds_at_measured_l2_hit_rate"] = t2
+        rg = pk["row_gather"][width]
+        if size == "table_96MB_fits_memory_side_cache":
+            pts = [(0.04, rg["table_96MB_fits_memory_side_cache"]), (0.25, rg["table_16MB_four_times_one_L2"]),
+                   (0.5, rg["table_8MB_twice_one_L2"]), (1.0, rg["table_2MB_fits_one_L2"])]
+            hh = min(max(h, pts[0][0]), 1.0)
+            for (h0, r0), (h1, r1) in zip(pts[:-1], pts[1:]):
+                if hh <= h1:
+                    rate = r0 + (r1 - r0) * (hh - h0) / (h1 - h0)
+                    break
+            t_g = g / (rate * 1e9)
+            out["gather_gbs_at_measured_l2_hit_rate"] = rate
+            out["l2_hit_model"] = "interpolated between the probe's tables of 1x, 2x, 4x and 24x one L2"
+        else:
+            t_g = g * h / (rg["table_2MB_fits_one_L2"] * 1e9) + g * (1.0 - h) / (gather_gbs * 1e9)
+            out["l2_hit_model"] = "hits at the L2-resident rate, then misses at the beyond-both rate"
+        out["seconds_at_measured_l2_hit_rate"] = stream_bytes / (pk["stream_read_2GiB"] * 1e9) + t_g
         out["l2_hit_rate_used"] = h
     return out
 
@@ -411,7 +429,8 @@ def main():
     if practical is not None:
         g = practical["row_gather"]
         log(f"[bench] practical peak: stream read {practical['stream_read_2GiB']:.0f} GB/s, copy {practical['copy_1GiB_read_plus_write']:.0f} GB/s, LDS reads {practical['lds_read_b128']:.0f} GB/s; "
-            + "; ".join(f"{w} gathers " + "/".join(f"{v:.0f}" for v in g[w].values()) for w in g) + " GB/s (L2 / memory-side cache / beyond)")
+            + "; ".join(f"{w} gathers " + "/".join(f"{v:.0f}" for v in g[w].values()) for w in g)
+            + " GB/s (table fits one L2 / 2x L2 / 4x L2 / fits the memory-side cache / beyond)")
 
     def run_config(cfg, steps, warmup, cold_steps):
         t0 = time.perf_counter()
